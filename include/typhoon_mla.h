@@ -1,0 +1,160 @@
+/*
+ * typhoon_mla.h -- C ABI of the MI355X (gfx950) TyphoonMLA decode library.
+ *
+ * One multi-head latent attention (MLA) decode step over a batch whose KV cache is a prefix
+ * shared by every request plus a per-request paged suffix (paper: Section 3.1, Algorithm 1).
+ * The shared prefix is attended in the naive formulation over per-head K/V expanded once from
+ * the latent cache (Algorithm 1 step 4), the suffix in the absorb formulation over the raw
+ * 576-wide latent rows (steps 5-7), and the partial softmaxes are merged exactly with their
+ * log-sum-exps (step 8).  `mode` also selects the two single-formulation baselines of Table 1.
+ *
+ * Conventions for every entry point
+ *   - Every data pointer is CALLER-OWNED DEVICE MEMORY, 16-byte aligned, dense in the stated
+ *     layout.  The library allocates nothing, keeps no state between calls, never synchronises
+ *     the host and enqueues work only on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream).  Results are ready when the stream reaches the end of the enqueued work.
+ *   - Return value: a tmla_status.  Arguments are validated on the host before anything is
+ *     launched, so argument errors are reported without touching the GPU.
+ *   - Supported dimensions: kv_lora_rank 512, qk_nope_dim 128, qk_rope_dim 64, v_head_dim 128
+ *     (DeepSeek-v3 / Kimi K2, Table 1), num_heads a multiple of 16, paged block_size 64 or 128.
+ *   - dtype TMLA_BF16: bf16 storage, fp32 accumulation and softmax.  TMLA_FP32: fp32 throughout.
+ *   - RoPE is applied by the caller: q[..., 128:192] and every cached rope part arrive rotated
+ *     (Algorithm 1 lists the query as "after W_Qb projection and RoPE").
+ *
+ * Expanded ("naive") cache layout -- what typhoon_mla_expand_* writes and decode reads.
+ *   TMLA_FP32: K [H, L, 192], V [H, L, 128], row-major.
+ *   TMLA_BF16: matrix-core operand order, so a tile is copied to LDS or registers verbatim.
+ *     Tokens are grouped in blocks of 32 (the last block zero-padded), NTB = ceil(L / 32).
+ *     K element (h, t, d), d in [0,192):
+ *        (((h*NTB + t/32)*12 + d/16)*64 + (t%32) + 32*((d%16)/8))*8 + d%8
+ *     V element (h, t, d), d in [0,128), with u = t%16:
+ *        ((((h*NTB + t/32)*2 + (t%32)/16)*4 + d/32)*64 + (d%32) + 32*((u/4)%2))*8 + 4*(u/8) + u%4
+ *     i.e. 6144 K elements and 4096 V elements per (head, 32-token block).
+ *   Use typhoon_mla_expanded_k_bytes / _v_bytes for the buffer sizes.
+ */
+#ifndef TYPHOON_MLA_H
+#define TYPHOON_MLA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TMLA_OK = 0,
+  TMLA_ERR_INVALID_ARG = 1,        /* null / negative / misaligned / inconsistent argument   */
+  TMLA_ERR_UNSUPPORTED = 2,        /* dimensions, head count, block size or dtype not built  */
+  TMLA_ERR_WORKSPACE_TOO_SMALL = 3,
+  TMLA_ERR_HIP = 4                 /* a launch failed; hipGetLastError() has the reason      */
+} tmla_status;
+
+typedef enum {
+  TMLA_MODE_MIXED = 0,       /* Algorithm 1: naive prefix + absorb suffix + LSE combine      */
+  TMLA_MODE_NAIVE_ONLY = 1,  /* Table 1 "Naive": expanded K/V for prefix and suffix           */
+  TMLA_MODE_ABSORB_ONLY = 2  /* Table 1 "Absorb": latent cache for prefix and suffix         */
+} tmla_mode;
+
+typedef enum { TMLA_BF16 = 0, TMLA_FP32 = 1 } tmla_dtype;
+
+typedef struct {
+  int32_t num_heads;      /* H                                   */
+  int32_t kv_lora_rank;   /* D_l = 512                           */
+  int32_t qk_nope_dim;    /* D_n = 128                           */
+  int32_t qk_rope_dim;    /* D_r = 64                            */
+  int32_t v_head_dim;     /* D_v = 128                           */
+  float sm_scale;         /* softmax scale on the full 192-wide score (e.g. 1/sqrt(192)) */
+  int32_t dtype;          /* tmla_dtype                          */
+} tmla_dims;
+
+/* Static text for a tmla_status (never NULL). */
+const char* typhoon_mla_status_string(int status);
+
+/* Bytes of the expanded K (resp. V) buffer for `num_tokens` tokens; 0 on invalid arguments. */
+size_t typhoon_mla_expanded_k_bytes(const tmla_dims* dims, int64_t num_tokens);
+size_t typhoon_mla_expanded_v_bytes(const tmla_dims* dims, int64_t num_tokens);
+
+/*
+ * Prefix expansion (Section 3.1 "Prefill": the shared part of the latent caches is expanded
+ * through the up-projection into per-head K and V):
+ *   K[h,t,:] = [ W_UK[h] c_t (128) ; r_t (64) ],  V[h,t,:] = W_UV[h] c_t (128).
+ *   prefix_ckv   in  [prefix_len, 512]     prefix_krope in  [prefix_len, 64]
+ *   w_uk, w_uv   in  [H, 128, 512]         (W_KVb1, W_KVb2 of Algorithm 1)
+ *   prefix_k / prefix_v  out, expanded layout above, typhoon_mla_expanded_{k,v}_bytes each.
+ * prefix_len == 0 is legal and launches nothing.
+ */
+int typhoon_mla_expand_prefix(const tmla_dims* dims, int32_t prefix_len,
+                              const void* prefix_ckv, const void* prefix_krope,
+                              const void* w_uk, const void* w_uv,
+                              void* prefix_k, void* prefix_v, void* stream);
+
+/*
+ * Same expansion applied to a whole paged pool of fused rows [num_blocks, block_size, 576]
+ * (latent 512 ++ rope 64); pool slot (p, j) becomes expanded token p*block_size + j.  Only
+ * TMLA_MODE_NAIVE_ONLY needs it (its Table 1 row reads expanded K/V for the suffix too).
+ * Slots holding garbage expand to garbage; decode never reads slots beyond a request's length.
+ */
+int typhoon_mla_expand_pool(const tmla_dims* dims, int32_t num_blocks, int32_t block_size,
+                            const void* suffix_pool, const void* w_uk, const void* w_uv,
+                            void* suffix_k_pool, void* suffix_v_pool, void* stream);
+
+/* Scratch bytes typhoon_mla_decode needs for this problem size (a pure host function). */
+size_t typhoon_mla_decode_workspace_bytes(const tmla_dims* dims, int32_t mode, int32_t batch,
+                                          int32_t q_len, int32_t prefix_len,
+                                          int32_t max_suffix_len);
+
+/*
+ * One decode step (Algorithm 1; Section 3.1 "Decode").
+ *   q            in  [B, q_len, H, 192]  noPE 128 ++ RoPE 64
+ *   prefix_k/_v  in  expanded prefix (mixed, naive_only; may be NULL otherwise or if prefix_len==0)
+ *   prefix_ckv   in  [prefix_len, 512], prefix_krope [prefix_len, 64] (absorb_only; else may be NULL)
+ *   suffix_pool  in  [num_blocks, block_size, 576] latent rows (mixed, absorb_only)
+ *   block_table  in  [B, max_blocks] int32 physical block of each logical suffix block;
+ *                    entries beyond ceil(suffix_lens[b]/block_size) are never read
+ *   suffix_lens  in  [B] int32 (device); 0 <= suffix_lens[b] <= max_suffix_len, which is a host
+ *                    upper bound with ceil(max_suffix_len/block_size) <= max_blocks
+ *   suffix_k_pool/_v_pool in expanded pool from typhoon_mla_expand_pool (naive_only; else NULL)
+ *   w_uk, w_uv   in  [H, 128, 512] (mixed, absorb_only)
+ *   out          out [B, q_len, H, 128] in dims->dtype
+ *   lse_out      out [B, q_len, H] fp32 natural-log LSE of the scaled scores, or NULL
+ *   workspace    scratch of at least typhoon_mla_decode_workspace_bytes(...), 256-byte aligned
+ * Visibility: every query sees the whole prefix; query position s of request b sees suffix
+ * tokens j <= suffix_lens[b] - q_len + s (the suffix already holds the q_len new tokens).
+ * A query that sees no token yields zeros and LSE = -inf.
+ */
+int typhoon_mla_decode(const tmla_dims* dims, int32_t mode, int32_t batch, int32_t q_len,
+                       const void* q, int32_t prefix_len,
+                       const void* prefix_k, const void* prefix_v,
+                       const void* prefix_ckv, const void* prefix_krope,
+                       const void* suffix_pool, int32_t num_blocks, int32_t block_size,
+                       const int32_t* block_table, int32_t max_blocks,
+                       const int32_t* suffix_lens, int32_t max_suffix_len,
+                       const void* suffix_k_pool, const void* suffix_v_pool,
+                       const void* w_uk, const void* w_uv,
+                       void* out, float* lse_out,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * CombineLSE alone (Algorithm 1 step 8; Section 3.2): exact merge of `num_partials` normalised
+ * partial outputs with their natural-log LSEs.
+ *   partial_out in [num_partials, rows, width] fp32,  partial_lse in [num_partials, rows] fp32
+ *   out         out [rows, width] in `out_dtype`,     lse_out out [rows] fp32 or NULL
+ * A partial with LSE = -inf contributes nothing (its values are ignored, NaN included).
+ * width must be a multiple of 4 and at most 512.
+ */
+int typhoon_mla_combine_lse(int32_t num_partials, int64_t rows, int32_t width,
+                            const float* partial_out, const float* partial_lse,
+                            void* out, int32_t out_dtype, float* lse_out, void* stream);
+
+/*
+ * Debug / tuning switches (process-wide, not thread-safe; default 0).
+ *   bit 0: run the scalar reference kernels instead of the matrix-core kernels for bf16.
+ * Returns the previous value.
+ */
+int typhoon_mla_set_debug_flags(int flags);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TYPHOON_MLA_H */

@@ -1,0 +1,276 @@
+// C ABI of the TyphoonMLA decode library: host-side argument validation, launch planning /
+// workspace layout, and dispatch to the kernels.  No HIP call is made before validation passes.
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+
+#include "tmla_common.hpp"
+
+namespace tmla {
+
+static int g_debug_flags = 0;
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static inline int round_up(int a, int b) { return ceil_div(a, b) * b; }
+
+static int env_int(const char* name, int dflt) {
+  const char* s = getenv(name);
+  if (!s || !*s) return dflt;
+  return atoi(s);
+}
+
+static int check_dims(const tmla_dims* d) {
+  if (!d) return TMLA_ERR_INVALID_ARG;
+  if (d->num_heads <= 0) return TMLA_ERR_INVALID_ARG;
+  if (d->dtype != TMLA_BF16 && d->dtype != TMLA_FP32) return TMLA_ERR_UNSUPPORTED;
+  if (d->kv_lora_rank != D_L || d->qk_nope_dim != D_N || d->qk_rope_dim != D_R ||
+      d->v_head_dim != D_V)
+    return TMLA_ERR_UNSUPPORTED;
+  if (d->num_heads % 16 != 0) return TMLA_ERR_UNSUPPORTED;
+  if (!(d->sm_scale > 0.f) || !(d->sm_scale < 1e30f)) return TMLA_ERR_INVALID_ARG;
+  return TMLA_OK;
+}
+
+static inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % a) != 0; }
+
+constexpr int NUM_CU = 256;  // MI355X compute units; work is cut to a small multiple of this
+
+// Cuts the call into work items (token chunks) and lays the intermediates out in the workspace.
+// Chunk counts per request are bounds derived from host-visible sizes only; a chunk that turns
+// out empty on the device reports LSE = -inf and is skipped by the combine step.
+int make_plan(const tmla_dims* dims, int mode, int B, int Sq, int Ls, int max_suffix,
+              int block_size, Plan* p) {
+  memset(p, 0, sizeof(*p));
+  p->B = B; p->Sq = Sq; p->H = dims->num_heads; p->Ls = Ls; p->max_suffix = max_suffix;
+  p->mode = mode; p->dtype = dims->dtype;
+  p->rows = (int64_t)B * Sq * dims->num_heads;
+  const int H = dims->num_heads;
+  const int M = B * Sq;
+  const int target = 2 * NUM_CU;
+
+  if (Ls > 0 && mode != TMLA_MODE_ABSORB_ONLY) {
+    // naive prefix pass: one workgroup owns a head and a block of up to 256 queries
+    const int wgs = std::max(1, H * ceil_div(M, 256));
+    int splits = env_int("TMLA_PREFIX_SPLITS", 0);
+    if (splits <= 0) splits = ceil_div(target, wgs);
+    splits = std::max(1, std::min(splits, ceil_div(Ls, 128)));
+    p->p_chunk = round_up(ceil_div(Ls, splits), TOK_BLK);
+    p->np_split = ceil_div(Ls, p->p_chunk);
+  }
+  if (mode == TMLA_MODE_NAIVE_ONLY && max_suffix > 0) {
+    int chunk = env_int("TMLA_NAIVE_SUFFIX_CHUNK", 0);
+    if (chunk <= 0) chunk = 1024;
+    p->ns_chunk = round_up(std::min(chunk, round_up(max_suffix, block_size)), block_size);
+    p->ns_chunks = ceil_div(max_suffix, p->ns_chunk);
+  }
+  if (mode != TMLA_MODE_NAIVE_ONLY) {
+    // absorb pass: one workgroup owns a request and up to 128 of its S_q*H query rows
+    const int wgs = std::max(1, B * ceil_div(Sq * H, 128));
+    if (mode == TMLA_MODE_ABSORB_ONLY && Ls > 0) {
+      int chunk = env_int("TMLA_ABSORB_PREFIX_CHUNK", 0);
+      if (chunk <= 0) chunk = std::max(512, round_up(ceil_div(Ls, std::max(1, ceil_div(2 * target, wgs))), 256));
+      p->ap_chunk = round_up(std::min(chunk, round_up(Ls, TOK_BLK)), TOK_BLK);
+      p->ap_chunks = ceil_div(Ls, p->ap_chunk);
+    }
+    if (max_suffix > 0) {
+      int chunk = env_int("TMLA_SUFFIX_CHUNK", 0);
+      if (chunk <= 0) {
+        const int want = std::max(1, ceil_div(2 * target, wgs));  // chunks per request wanted
+        chunk = std::max(256, ceil_div(max_suffix, want));
+      }
+      p->as_chunk = round_up(std::min(chunk, round_up(max_suffix, block_size)), block_size);
+      p->as_chunks = ceil_div(max_suffix, p->as_chunk);
+    }
+  }
+  p->n_naive = p->np_split + p->ns_chunks;
+  p->n_lat = p->ap_chunks + p->as_chunks;
+
+  const size_t esz = dims->dtype == TMLA_BF16 ? 2 : 4;
+  size_t off = 0;
+  p->off_qabs = off;      off = align_up(off + (p->n_lat ? (size_t)p->rows * D_ROW * esz : 0), 256);
+  p->off_naive_o = off;   off = align_up(off + (size_t)p->n_naive * p->rows * D_V * 4, 256);
+  p->off_naive_lse = off; off = align_up(off + (size_t)p->n_naive * p->rows * 4, 256);
+  p->off_lat_o = off;     off = align_up(off + (size_t)p->n_lat * p->rows * D_L * 4, 256);
+  p->off_lat_lse = off;   off = align_up(off + (size_t)p->n_lat * p->rows * 4, 256);
+  p->total = off + 256;
+  return TMLA_OK;
+}
+
+static int64_t padded_tokens(const tmla_dims* dims, int64_t n) {
+  return dims->dtype == TMLA_BF16 ? (n + TOK_BLK - 1) / TOK_BLK * TOK_BLK : n;
+}
+
+}  // namespace tmla
+
+using namespace tmla;
+
+extern "C" {
+
+const char* typhoon_mla_status_string(int status) {
+  switch (status) {
+    case TMLA_OK: return "ok";
+    case TMLA_ERR_INVALID_ARG: return "invalid argument";
+    case TMLA_ERR_UNSUPPORTED: return "unsupported dimensions, head count, block size or dtype";
+    case TMLA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case TMLA_ERR_HIP: return "HIP launch error";
+    default: return "unknown status";
+  }
+}
+
+int typhoon_mla_set_debug_flags(int flags) {
+  const int old = g_debug_flags;
+  g_debug_flags = flags;
+  return old;
+}
+
+size_t typhoon_mla_expanded_k_bytes(const tmla_dims* dims, int64_t num_tokens) {
+  if (check_dims(dims) != TMLA_OK || num_tokens < 0) return 0;
+  const size_t esz = dims->dtype == TMLA_BF16 ? 2 : 4;
+  return (size_t)dims->num_heads * padded_tokens(dims, num_tokens) * D_QK * esz;
+}
+size_t typhoon_mla_expanded_v_bytes(const tmla_dims* dims, int64_t num_tokens) {
+  if (check_dims(dims) != TMLA_OK || num_tokens < 0) return 0;
+  const size_t esz = dims->dtype == TMLA_BF16 ? 2 : 4;
+  return (size_t)dims->num_heads * padded_tokens(dims, num_tokens) * D_V * esz;
+}
+
+static int expand_common(const tmla_dims* dims, int64_t ntok, const void* c, int64_t c_stride,
+                         const void* r, int64_t r_stride, const void* w_uk, const void* w_uv,
+                         void* k_out, void* v_out, void* stream) {
+  if (ntok == 0) return TMLA_OK;
+  if (!c || !r || !w_uk || !w_uv || !k_out || !v_out) return TMLA_ERR_INVALID_ARG;
+  if (misaligned(c, 16) || misaligned(r, 16) || misaligned(w_uk, 16) || misaligned(w_uv, 16) ||
+      misaligned(k_out, 16) || misaligned(v_out, 16))
+    return TMLA_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  (void)hipGetLastError();
+  if (dims->dtype == TMLA_FP32) {
+    simple_expand<float>(dims->num_heads, ntok, (const float*)c, c_stride, (const float*)r,
+                         r_stride, (const float*)w_uk, (const float*)w_uv, (float*)k_out,
+                         (float*)v_out, st);
+  } else {
+    simple_expand<bf16_t>(dims->num_heads, ntok, (const bf16_t*)c, c_stride, (const bf16_t*)r,
+                          r_stride, (const bf16_t*)w_uk, (const bf16_t*)w_uv, (bf16_t*)k_out,
+                          (bf16_t*)v_out, st);
+  }
+  return hipGetLastError() == hipSuccess ? TMLA_OK : TMLA_ERR_HIP;
+}
+
+int typhoon_mla_expand_prefix(const tmla_dims* dims, int32_t prefix_len, const void* prefix_ckv,
+                              const void* prefix_krope, const void* w_uk, const void* w_uv,
+                              void* prefix_k, void* prefix_v, void* stream) {
+  const int st = check_dims(dims);
+  if (st != TMLA_OK) return st;
+  if (prefix_len < 0) return TMLA_ERR_INVALID_ARG;
+  return expand_common(dims, prefix_len, prefix_ckv, D_L, prefix_krope, D_R, w_uk, w_uv, prefix_k,
+                       prefix_v, stream);
+}
+
+int typhoon_mla_expand_pool(const tmla_dims* dims, int32_t num_blocks, int32_t block_size,
+                            const void* suffix_pool, const void* w_uk, const void* w_uv,
+                            void* suffix_k_pool, void* suffix_v_pool, void* stream) {
+  const int st = check_dims(dims);
+  if (st != TMLA_OK) return st;
+  if (num_blocks < 0) return TMLA_ERR_INVALID_ARG;
+  if (block_size != 64 && block_size != 128) return TMLA_ERR_UNSUPPORTED;
+  const size_t esz = dims->dtype == TMLA_BF16 ? 2 : 4;
+  const char* rope = suffix_pool ? (const char*)suffix_pool + D_L * esz : nullptr;
+  return expand_common(dims, (int64_t)num_blocks * block_size, suffix_pool, D_ROW, rope, D_ROW,
+                       w_uk, w_uv, suffix_k_pool, suffix_v_pool, stream);
+}
+
+static int check_decode_sizes(const tmla_dims* dims, int mode, int batch, int q_len,
+                              int prefix_len, int max_suffix_len) {
+  const int st = check_dims(dims);
+  if (st != TMLA_OK) return st;
+  if (mode != TMLA_MODE_MIXED && mode != TMLA_MODE_NAIVE_ONLY && mode != TMLA_MODE_ABSORB_ONLY)
+    return TMLA_ERR_INVALID_ARG;
+  if (batch < 0 || q_len <= 0 || prefix_len < 0 || max_suffix_len < 0) return TMLA_ERR_INVALID_ARG;
+  if (q_len > 8) return TMLA_ERR_UNSUPPORTED;
+  if ((int64_t)batch * q_len * dims->num_heads > (int64_t)1 << 30) return TMLA_ERR_UNSUPPORTED;
+  return TMLA_OK;
+}
+
+size_t typhoon_mla_decode_workspace_bytes(const tmla_dims* dims, int32_t mode, int32_t batch,
+                                          int32_t q_len, int32_t prefix_len,
+                                          int32_t max_suffix_len) {
+  if (check_decode_sizes(dims, mode, batch, q_len, prefix_len, max_suffix_len) != TMLA_OK) return 0;
+  Plan p;
+  // the plan rounds suffix chunks to the paged block size; 128 covers both supported sizes
+  make_plan(dims, mode, batch, q_len, prefix_len, max_suffix_len, 128, &p);
+  size_t a = p.total;
+  make_plan(dims, mode, batch, q_len, prefix_len, max_suffix_len, 64, &p);
+  return std::max(a, p.total);
+}
+
+int typhoon_mla_decode(const tmla_dims* dims, int32_t mode, int32_t batch, int32_t q_len,
+                       const void* q, int32_t prefix_len, const void* prefix_k,
+                       const void* prefix_v, const void* prefix_ckv, const void* prefix_krope,
+                       const void* suffix_pool, int32_t num_blocks, int32_t block_size,
+                       const int32_t* block_table, int32_t max_blocks, const int32_t* suffix_lens,
+                       int32_t max_suffix_len, const void* suffix_k_pool,
+                       const void* suffix_v_pool, const void* w_uk, const void* w_uv, void* out,
+                       float* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
+  int st = check_decode_sizes(dims, mode, batch, q_len, prefix_len, max_suffix_len);
+  if (st != TMLA_OK) return st;
+  if (block_size != 64 && block_size != 128) return TMLA_ERR_UNSUPPORTED;
+  if (num_blocks < 0 || max_blocks < 0) return TMLA_ERR_INVALID_ARG;
+  if ((int64_t)max_blocks * block_size < max_suffix_len) return TMLA_ERR_INVALID_ARG;
+  if (batch == 0) return TMLA_OK;
+  if (!q || !out || !suffix_lens) return TMLA_ERR_INVALID_ARG;
+  const bool need_naive_prefix = prefix_len > 0 && mode != TMLA_MODE_ABSORB_ONLY;
+  const bool need_latent_prefix = prefix_len > 0 && mode == TMLA_MODE_ABSORB_ONLY;
+  const bool need_latent_suffix = max_suffix_len > 0 && mode != TMLA_MODE_NAIVE_ONLY;
+  const bool need_naive_suffix = max_suffix_len > 0 && mode == TMLA_MODE_NAIVE_ONLY;
+  if (need_naive_prefix && (!prefix_k || !prefix_v)) return TMLA_ERR_INVALID_ARG;
+  if (need_latent_prefix && (!prefix_ckv || !prefix_krope)) return TMLA_ERR_INVALID_ARG;
+  if (need_latent_suffix && (!suffix_pool || !block_table || num_blocks == 0))
+    return TMLA_ERR_INVALID_ARG;
+  if (need_naive_suffix && (!suffix_k_pool || !suffix_v_pool || !block_table || num_blocks == 0))
+    return TMLA_ERR_INVALID_ARG;
+  if ((need_latent_prefix || need_latent_suffix) && (!w_uk || !w_uv)) return TMLA_ERR_INVALID_ARG;
+  const void* ptrs[] = {q, out, prefix_k, prefix_v, prefix_ckv, prefix_krope, suffix_pool,
+                        suffix_k_pool, suffix_v_pool, w_uk, w_uv};
+  for (const void* ptr : ptrs)
+    if (ptr && misaligned(ptr, 16)) return TMLA_ERR_INVALID_ARG;
+  if (misaligned(block_table, 4) || misaligned(suffix_lens, 4) || misaligned(lse_out, 4))
+    return TMLA_ERR_INVALID_ARG;
+
+  Plan p;
+  make_plan(dims, mode, batch, q_len, prefix_len, max_suffix_len, block_size, &p);
+  if (!workspace || misaligned(workspace, 256)) return TMLA_ERR_INVALID_ARG;
+  if (workspace_bytes < p.total) return TMLA_ERR_WORKSPACE_TOO_SMALL;
+
+  DecodeArgs a;
+  a.q = q; a.prefix_k = prefix_k; a.prefix_v = prefix_v; a.prefix_ckv = prefix_ckv;
+  a.prefix_krope = prefix_krope; a.suffix_pool = suffix_pool; a.block_table = block_table;
+  a.suffix_lens = suffix_lens; a.suffix_k_pool = suffix_k_pool; a.suffix_v_pool = suffix_v_pool;
+  a.w_uk = w_uk; a.w_uv = w_uv; a.out = out; a.lse_out = lse_out; a.ws = (char*)workspace;
+  a.num_blocks = num_blocks; a.block_size = block_size; a.max_blocks = max_blocks;
+  a.sm_scale = dims->sm_scale; a.stream = (hipStream_t)stream;
+
+  (void)hipGetLastError();
+  if (dims->dtype == TMLA_FP32) simple_decode<float>(p, a);
+  else simple_decode<bf16_t>(p, a);
+  return hipGetLastError() == hipSuccess ? TMLA_OK : TMLA_ERR_HIP;
+}
+
+int typhoon_mla_combine_lse(int32_t num_partials, int64_t rows, int32_t width,
+                            const float* partial_out, const float* partial_lse, void* out,
+                            int32_t out_dtype, float* lse_out, void* stream) {
+  if (num_partials <= 0 || rows < 0 || width <= 0) return TMLA_ERR_INVALID_ARG;
+  if (width % 4 != 0 || width > 512) return TMLA_ERR_UNSUPPORTED;
+  if (out_dtype != TMLA_BF16 && out_dtype != TMLA_FP32) return TMLA_ERR_UNSUPPORTED;
+  if (rows == 0) return TMLA_OK;
+  if (!partial_out || !partial_lse || !out) return TMLA_ERR_INVALID_ARG;
+  if (misaligned(partial_out, 16) || misaligned(out, 8) || misaligned(partial_lse, 4) ||
+      misaligned(lse_out, 4))
+    return TMLA_ERR_INVALID_ARG;
+  (void)hipGetLastError();
+  launch_combine_lse(num_partials, rows, width, partial_out, partial_lse, out, out_dtype, lse_out,
+                     (hipStream_t)stream);
+  return hipGetLastError() == hipSuccess ? TMLA_OK : TMLA_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,135 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 oracle, element by element, on
+seeded inputs small enough for the oracle yet spanning several tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mla_oracle as O
+from paper_2509_21081_amd import binding as T
+from paper_2509_21081_amd import workloads as W
+from tests import helpers as Hh
+
+pytestmark = pytest.mark.gpu
+
+MODES = ["mixed", "naive_only", "absorb_only"]
+
+# (name, kwargs for small_spec)
+SMALL_CASES = {
+    "ragged_h16": dict(batch=3, heads=16, q_len=1, prefix_len=100, suffix_min=0, suffix_max=150),
+    "mtp_h32": dict(batch=2, heads=32, q_len=2, prefix_len=70, suffix_min=1, suffix_max=200,
+                    seed=21),
+    "no_prefix": dict(batch=4, heads=16, q_len=1, prefix_len=0, suffix_min=1, suffix_max=130,
+                      seed=22),
+    "no_suffix": dict(batch=2, heads=16, q_len=1, prefix_len=97, suffix_min=0, suffix_max=0,
+                      seed=23),
+    "block128_qlen3": dict(batch=2, heads=16, q_len=3, prefix_len=33, suffix_min=0, suffix_max=260,
+                           block_size=128, seed=24),
+    "peaked": dict(batch=2, heads=16, q_len=1, prefix_len=150, suffix_min=20, suffix_max=90,
+                   seed=25, q_gain=8.0),
+    "h128_many_tiles": dict(batch=5, heads=128, q_len=1, prefix_len=300, suffix_min=40,
+                            suffix_max=330, seed=26),
+    "wide_batch": dict(batch=70, heads=16, q_len=1, prefix_len=130, suffix_min=0, suffix_max=70,
+                       seed=27),
+}
+
+_cache = {}
+
+
+def _workload_and_ref(case, dtype):
+    key = (case, dtype)
+    if key not in _cache:
+        wl = W.make_workload(W.small_spec(name=case, dtype=dtype, **SMALL_CASES[case]))
+        ref = O.mla_decode_definition(**wl.as_float64())
+        _cache[key] = (wl, ref)
+    return _cache[key]
+
+
+@pytest.mark.parametrize("flags", [0, 1], ids=["mfma", "scalar"])
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("case", list(SMALL_CASES))
+def test_small_cases(case, dtype, mode, flags, gpu_device):
+    if dtype == "fp32" and flags == 1:
+        pytest.skip("fp32 always runs the scalar kernels")
+    wl, (ref, ref_lse) = _workload_and_ref(case, dtype)
+    print(f"case={case} dtype={dtype} mode={mode} flags={flags}", flush=True)
+    got, got_lse = Hh.run_library(wl, mode, gpu_device, flags=flags)
+    Hh.assert_parity(got, got_lse, ref, ref_lse, dtype, f"{case}/{dtype}/{mode}",
+                     logit_gain=wl.spec.q_gain)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+@pytest.mark.parametrize("ntok", [1, 31, 64, 100])
+def test_expand_prefix_matches_definition(dtype, ntok, gpu_device):
+    wl = W.make_workload(W.small_spec(dtype=dtype, batch=1, heads=16, prefix_len=ntok,
+                                      suffix_min=1, suffix_max=1, seed=40 + ntok))
+    a = wl.as_float64()
+    k_ref, v_ref = O.expand_prefix_definition(a["prefix_ckv"], a["prefix_krope"], a["w_uk"],
+                                              a["w_uv"])
+    d = wl.to(gpu_device)
+    dims = Hh.dims_of(wl)
+    print(f"expand dtype={dtype} ntok={ntok}", flush=True)
+    pk, pv = T.typhoon_mla_expand_prefix(dims, d.prefix_ckv, d.prefix_krope, d.w_uk, d.w_uv)
+    torch.cuda.synchronize()
+    K, V = Hh.unpack_expanded(pk, pv, 16, ntok, dtype)
+    rt = 2.0 ** -8 if dtype == "bf16" else 1e-5      # one bf16 rounding of an fp32 accumulation
+    np.testing.assert_allclose(K, k_ref, rtol=rt, atol=1e-3 if dtype == "bf16" else 1e-6)
+    np.testing.assert_allclose(V, v_ref, rtol=rt, atol=1e-3 if dtype == "bf16" else 1e-6)
+    # the rope part is a verbatim copy
+    np.testing.assert_array_equal(K[:, :, 128:], np.broadcast_to(a["prefix_krope"], (16, ntok, 64)))
+    if dtype == "bf16" and ntok % 32:
+        # padding tokens of the last 32-token block are zero
+        kraw = pk.view(torch.bfloat16).double().cpu().numpy()
+        hh, dd = np.meshgrid(np.arange(16), np.arange(192), indexing="ij")
+        ntb32 = (ntok + 31) // 32 * 32
+        for t in range(ntok, ntb32):
+            assert np.all(kraw[Hh.k_offset(hh, ntb32, t, dd, dtype)] == 0)
+
+
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("n,rows,width", [(1, 5, 128), (3, 130, 128), (7, 33, 512), (2, 1, 4)])
+def test_combine_lse_matches_definition(n, rows, width, out_dtype, gpu_device):
+    g = torch.Generator().manual_seed(n * 1000 + rows)
+    po = torch.randn((n, rows, width), generator=g)
+    pl = torch.randn((n, rows), generator=g) * 4
+    # sprinkle empty partials (LSE = -inf with NaN payload) and one fully empty row
+    pl[0, ::3] = float("-inf")
+    po[0, ::3] = float("nan")
+    if rows > 1:
+        pl[:, 1] = float("-inf")
+    ref_o, ref_l = O.combine_lse(po.double().numpy(), pl.double().numpy())
+    print(f"combine n={n} rows={rows} width={width} {out_dtype}", flush=True)
+    out, lse = T.typhoon_mla_combine_lse(po.to(gpu_device), pl.to(gpu_device), out_dtype)
+    torch.cuda.synchronize()
+    tol = 1e-5 if out_dtype == torch.float32 else 2.0 ** -8
+    np.testing.assert_allclose(out.double().cpu().numpy(), ref_o, rtol=tol, atol=1e-6)
+    got_l = lse.double().cpu().numpy()
+    assert np.array_equal(np.isneginf(got_l), np.isneginf(ref_l))
+    fin = np.isfinite(ref_l)
+    np.testing.assert_allclose(got_l[fin], ref_l[fin], atol=1e-5, rtol=1e-6)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_bitwise_repeatable(mode, gpu_device):
+    wl, _ = _workload_and_ref("ragged_h16", "bf16")
+    a = Hh.run_library(wl, mode, gpu_device)
+    b = Hh.run_library(wl, mode, gpu_device)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_cfg1_tiny_fp32_full(mode, gpu_device):
+    wl = W.make_workload(W.CONFIGS["cfg1_tiny_fp32"])
+    ref, ref_lse = O.mla_decode_definition(**wl.as_float64())
+    print(f"cfg1 mode={mode}", flush=True)
+    got, got_lse = Hh.run_library(wl, mode, gpu_device)
+    Hh.assert_parity(got, got_lse, ref, ref_lse, "fp32", f"cfg1/{mode}")
+
+
+def test_modes_agree_with_each_other(gpu_device):
+    wl, _ = _workload_and_ref("mtp_h32", "bf16")
+    outs = {m: Hh.run_library(wl, m, gpu_device) for m in MODES}
+    for m in MODES[1:]:
+        np.testing.assert_allclose(outs[m][0], outs["mixed"][0], atol=1e-2, rtol=2e-2)
+        fin = np.isfinite(outs["mixed"][1])
+        np.testing.assert_allclose(outs[m][1][fin], outs["mixed"][1][fin], atol=2e-3)

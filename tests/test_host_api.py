@@ -1,0 +1,138 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, validates its
+arguments on the host (no launch happens on an error path) and sizes its buffers sensibly."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2509_21081_amd import binding as T
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _dims(**kw):
+    d = dict(num_heads=16, sm_scale=0.07, dtype=T.BF16)
+    d.update(kw)
+    return T.make_dims(**d)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "typhoon_mla.h")).read()
+    declared = set(re.findall(r"\b(typhoon_mla_\w+)\s*\(", header))
+    assert declared == set(T.EXPORTS)
+    L = T.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_status_strings():
+    assert T.typhoon_mla_status_string(0) == "ok"
+    for s in range(1, 5):
+        assert T.typhoon_mla_status_string(s) not in ("ok", "unknown status")
+    assert T.typhoon_mla_status_string(99) == "unknown status"
+
+
+def test_expanded_sizes():
+    d = _dims(num_heads=128)
+    # bf16: 640 bytes per token-head, tokens padded to 32 (Table 1: L_s H (D_qk + D_v) words)
+    assert T.typhoon_mla_expanded_k_bytes(d, 4096) == 128 * 4096 * 192 * 2
+    assert T.typhoon_mla_expanded_v_bytes(d, 4096) == 128 * 4096 * 128 * 2
+    assert T.typhoon_mla_expanded_k_bytes(d, 33) == 128 * 64 * 192 * 2
+    f = _dims(num_heads=16, dtype=T.FP32)
+    assert T.typhoon_mla_expanded_k_bytes(f, 33) == 16 * 33 * 192 * 4
+    assert T.typhoon_mla_expanded_k_bytes(_dims(kv_lora_rank=256), 10) == 0
+
+
+def test_dims_validation():
+    L = T.lib()
+    P = ctypes.byref
+    nul = ctypes.c_void_p(None)
+    one = ctypes.c_void_p(4096)  # never dereferenced: validation fails first
+    assert L.typhoon_mla_expand_prefix(None, 4, one, one, one, one, one, one, nul) == \
+        T.TMLA_ERR_INVALID_ARG
+    for bad in (dict(kv_lora_rank=256), dict(qk_nope_dim=64), dict(num_heads=24), dict(dtype=7)):
+        assert L.typhoon_mla_expand_prefix(P(_dims(**bad)), 4, one, one, one, one, one, one, nul) \
+            == T.TMLA_ERR_UNSUPPORTED, bad
+    assert L.typhoon_mla_expand_prefix(P(_dims(num_heads=0)), 4, one, one, one, one, one, one,
+                                       nul) == T.TMLA_ERR_INVALID_ARG
+    assert L.typhoon_mla_expand_prefix(P(_dims(sm_scale=-1.0)), 4, one, one, one, one, one, one,
+                                       nul) == T.TMLA_ERR_INVALID_ARG
+    d = _dims()
+    assert L.typhoon_mla_expand_prefix(P(d), -1, one, one, one, one, one, one, nul) == \
+        T.TMLA_ERR_INVALID_ARG
+    assert L.typhoon_mla_expand_prefix(P(d), 4, nul, one, one, one, one, one, nul) == \
+        T.TMLA_ERR_INVALID_ARG
+    assert L.typhoon_mla_expand_prefix(P(d), 4, ctypes.c_void_p(4100), one, one, one, one, one,
+                                       nul) == T.TMLA_ERR_INVALID_ARG        # misaligned
+    assert L.typhoon_mla_expand_prefix(P(d), 0, nul, nul, nul, nul, nul, nul, nul) == T.TMLA_OK
+    assert L.typhoon_mla_expand_pool(P(d), 3, 48, one, one, one, one, one, nul) == \
+        T.TMLA_ERR_UNSUPPORTED
+
+
+def _decode(L, d, mode=0, batch=2, q_len=1, prefix_len=64, max_suffix=100, block_size=64,
+            max_blocks=2, ws_bytes=None, **ptr_overrides):
+    one = ctypes.c_void_p(4096)
+    names = ["q", "prefix_k", "prefix_v", "prefix_ckv", "prefix_krope", "suffix_pool",
+             "block_table", "suffix_lens", "suffix_k_pool", "suffix_v_pool", "w_uk", "w_uv", "out",
+             "lse_out", "workspace"]
+    p = {n: one for n in names}
+    for k, v in ptr_overrides.items():
+        p[k] = ctypes.c_void_p(v)
+    if ws_bytes is None:
+        ws_bytes = T.typhoon_mla_decode_workspace_bytes(d, mode, batch, q_len, prefix_len,
+                                                        max_suffix)
+    return L.typhoon_mla_decode(
+        ctypes.byref(d), mode, batch, q_len, p["q"], prefix_len, p["prefix_k"], p["prefix_v"],
+        p["prefix_ckv"], p["prefix_krope"], p["suffix_pool"], 8, block_size, p["block_table"],
+        max_blocks, p["suffix_lens"], max_suffix, p["suffix_k_pool"], p["suffix_v_pool"],
+        p["w_uk"], p["w_uv"], p["out"], p["lse_out"], p["workspace"], ws_bytes, None)
+
+
+def test_decode_validation_without_gpu():
+    L = T.lib()
+    d = _dims()
+    assert _decode(L, d, mode=5) == T.TMLA_ERR_INVALID_ARG
+    assert _decode(L, d, q_len=0) == T.TMLA_ERR_INVALID_ARG
+    assert _decode(L, d, q_len=9) == T.TMLA_ERR_UNSUPPORTED
+    assert _decode(L, d, batch=-1) == T.TMLA_ERR_INVALID_ARG
+    assert _decode(L, d, prefix_len=-3) == T.TMLA_ERR_INVALID_ARG
+    assert _decode(L, d, block_size=32) == T.TMLA_ERR_UNSUPPORTED
+    assert _decode(L, d, max_suffix=200, max_blocks=2) == T.TMLA_ERR_INVALID_ARG  # 2*64 < 200
+    assert _decode(L, d, q=None) == T.TMLA_ERR_INVALID_ARG
+    assert _decode(L, d, out=None) == T.TMLA_ERR_INVALID_ARG
+    assert _decode(L, d, suffix_lens=None) == T.TMLA_ERR_INVALID_ARG
+    assert _decode(L, d, prefix_k=None) == T.TMLA_ERR_INVALID_ARG                # mixed needs it
+    assert _decode(L, d, mode=2, prefix_ckv=None) == T.TMLA_ERR_INVALID_ARG      # absorb_only
+    assert _decode(L, d, mode=1, suffix_k_pool=None) == T.TMLA_ERR_INVALID_ARG   # naive_only
+    assert _decode(L, d, suffix_pool=None) == T.TMLA_ERR_INVALID_ARG
+    assert _decode(L, d, w_uk=None) == T.TMLA_ERR_INVALID_ARG
+    assert _decode(L, d, q=4104) == T.TMLA_ERR_INVALID_ARG                        # misaligned
+    assert _decode(L, d, workspace=None) == T.TMLA_ERR_INVALID_ARG
+    assert _decode(L, d, workspace=4096 + 64) == T.TMLA_ERR_INVALID_ARG           # needs 256 B
+    assert _decode(L, d, ws_bytes=128) == T.TMLA_ERR_WORKSPACE_TOO_SMALL
+    assert _decode(L, d, batch=0) == T.TMLA_OK                                    # nothing to do
+
+
+def test_workspace_bytes_monotone_and_zero_on_error():
+    d = _dims(num_heads=128)
+    assert T.typhoon_mla_decode_workspace_bytes(d, 7, 4, 1, 10, 10) == 0
+    small = T.typhoon_mla_decode_workspace_bytes(d, T.MODE_MIXED, 4, 1, 256, 64)
+    big = T.typhoon_mla_decode_workspace_bytes(d, T.MODE_MIXED, 64, 1, 4096, 512)
+    assert 0 < small < big
+    # the absorbed queries alone need B*S_q*H*576 elements
+    assert big >= 64 * 128 * 576 * 2
+
+
+def test_combine_validation():
+    L = T.lib()
+    one = ctypes.c_void_p(4096)
+    assert L.typhoon_mla_combine_lse(0, 4, 128, one, one, one, 1, None, None) == \
+        T.TMLA_ERR_INVALID_ARG
+    assert L.typhoon_mla_combine_lse(2, 4, 130, one, one, one, 1, None, None) == \
+        T.TMLA_ERR_UNSUPPORTED
+    assert L.typhoon_mla_combine_lse(2, 4, 1024, one, one, one, 1, None, None) == \
+        T.TMLA_ERR_UNSUPPORTED
+    assert L.typhoon_mla_combine_lse(2, 4, 128, None, one, one, 1, None, None) == \
+        T.TMLA_ERR_INVALID_ARG
+    assert L.typhoon_mla_combine_lse(2, 0, 128, None, None, None, 1, None, None) == T.TMLA_OK
