@@ -1,0 +1,263 @@
+#!/usr/bin/env python3
+"""Benchmark of the TyphoonMLA decode hot path on one MI355X.
+
+A "step" is one pass of the whole hot path -- typhoon_mla_decode in mixed mode: naive prefix
+attention, query absorption, absorb suffix attention, up-projection and LSE combine -- over one
+batch of seeded synthetic input already resident in HBM.  The one-off prefix expansion is timed
+separately.  Prints ONE JSON line (see README for the fields).
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2_dsv3_b64]
+                  [--modes mixed,absorb_only,naive_only] [--no-cpu-baseline] [--no-stages]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12          # B/s, MI355X published
+MFMA_BF16_PEAK = 2.5e15    # FLOP/s dense bf16, MI355X published
+
+STAGES = {"prefix_attention": 0x10, "naive_suffix_attention": 0x20, "query_absorb": 0x40,
+          "absorb_attention": 0x80, "upproj_combine": 0x100}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg2_dsv3_b64")
+    ap.add_argument("--modes", default="mixed,absorb_only,naive_only")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stages", action="store_true")
+    ap.add_argument("--cpu-sample-requests", type=int, default=0,
+                    help="requests (all heads each) in the oracle sample; 0 = auto")
+    return ap.parse_args()
+
+
+def time_steps(fn, steps, warmup, torch):
+    """Wall-clock ms per call over `steps` calls, synchronised on both sides."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def event_time(fn, steps, warmup, torch):
+    """Average device time per call (HIP events on the stream the kernels run on)."""
+    for _ in range(warmup):
+        fn()
+    stream = torch.cuda.current_stream()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(steps):
+        fn()
+    e1.record(stream)
+    e1.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def read_traffic(workload, kernel):
+    """HBM bytes per launch measured with rocprofv3 --pmc (profiles/hbm_traffic.txt), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 3 and f[0] == workload and f[1] == kernel:
+            try:
+                return float(f[2])
+            except ValueError:
+                return None
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding or collectives are part of "
+              "it); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2509_21081_amd import binding as T
+    from paper_2509_21081_amd import cost_model as C
+    from paper_2509_21081_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    T.lib()  # fail loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    spec = W.CONFIGS[args.workload]
+    t0 = time.perf_counter()
+    wl = W.make_workload(spec, poison=True)
+    gen_s = time.perf_counter() - t0
+    d = wl.to(dev)
+    dims = T.make_dims(spec.heads, wl.sm_scale, spec.dtype)
+    B, S, H, L_s = spec.batch, spec.q_len, spec.heads, spec.prefix_len
+    sum_ln = int(wl.suffix_lens.sum())
+    shape = C.Shape(B, S, H, L_s, sum_ln, 2 if spec.dtype == "bf16" else 4)
+    modes = [m for m in args.modes.split(",") if m]
+    if "mixed" not in modes:
+        modes = ["mixed"] + modes
+
+    # one-off prefix expansion (prefill-time cost, Section 3.1), timed separately
+    pk = pv = None
+    expand_ms = None
+    if L_s > 0:
+        pk, pv = T.typhoon_mla_expand_prefix(dims, d.prefix_ckv, d.prefix_krope, d.w_uk, d.w_uv)
+        expand_ms = event_time(lambda: T.typhoon_mla_expand_prefix(
+            dims, d.prefix_ckv, d.prefix_krope, d.w_uk, d.w_uv, pk, pv), 3, 1, torch)
+    sk = sv = None
+    if "naive_only" in modes:
+        sk, sv = T.typhoon_mla_expand_pool(dims, d.pool, d.w_uk, d.w_uv)
+
+    out = torch.empty((B, S, H, 128), dtype=d.q.dtype, device=dev)
+    lse = torch.empty((B, S, H), dtype=torch.float32, device=dev)
+    ws = {}
+    for m in modes:
+        nbytes = T.typhoon_mla_decode_workspace_bytes(dims, T.MODES[m], B, S, L_s,
+                                                      wl.max_suffix_len)
+        ws[m] = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+
+    def step(mode):
+        T.typhoon_mla_decode(dims, mode, d.q, L_s, prefix_k=pk, prefix_v=pv,
+                             prefix_ckv=d.prefix_ckv, prefix_krope=d.prefix_krope,
+                             suffix_pool=d.pool, block_table=d.block_table,
+                             suffix_lens=d.suffix_lens, max_suffix_len=wl.max_suffix_len,
+                             suffix_k_pool=sk, suffix_v_pool=sv, w_uk=d.w_uk, w_uv=d.w_uv,
+                             out=out, lse_out=lse, workspace=ws[mode])
+
+    # ---- the timed region: exactly K steps of the whole hot path, inputs resident in HBM
+    ms = {}
+    ms["mixed"] = time_steps(lambda: step("mixed"), args.steps, args.warmup, torch)
+    got = out.double().cpu().numpy()
+    got_lse = lse.double().cpu().numpy()
+    for m in modes:
+        if m != "mixed":
+            k = max(3, args.steps // 5)
+            ms[m] = time_steps(lambda: step(m), k, max(1, args.warmup // 5), torch)
+
+    # ---- per-kernel device time (mixed mode), for the roofline of the dominant kernel
+    stage_ms = {}
+    if not args.no_stages and spec.dtype == "bf16":
+        step("mixed")
+        for name, bit in STAGES.items():
+            if name == "naive_suffix_attention":
+                continue
+            if name == "prefix_attention" and L_s == 0:
+                continue
+            T.typhoon_mla_set_debug_flags(bit)
+            try:
+                stage_ms[name] = event_time(lambda: step("mixed"), args.steps, 3, torch)
+            finally:
+                T.typhoon_mla_set_debug_flags(0)
+    tokens = B * S
+    flops_mixed = 2 * C.table1_macs(shape, "mixed") + 2 * C.projection_macs(shape)
+    result = {
+        "metric": "MLA decode tokens/s (mixed naive-prefix + absorb-suffix attention, one layer)",
+        "value": tokens / (ms["mixed"] * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms["mixed"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": spec.dtype, "data": "synthetic (seeded N(0,1) latents and queries, "
+                                     "N(0,0.02) up-projections)",
+        "config": {"workload": spec.name, "batch": B, "q_len": S, "heads": H, "prefix_len": L_s,
+                   "suffix_tokens_total": sum_ln, "suffix_len_range": [spec.suffix_min,
+                                                                       spec.suffix_max],
+                   "block_size": spec.block_size, "seed": spec.seed},
+        "tflops": flops_mixed / (ms["mixed"] * 1e-3) / 1e12,
+        "ms_per_step_by_mode": ms,
+        "speedup_vs_absorb_only": (ms["absorb_only"] / ms["mixed"]) if "absorb_only" in ms else None,
+        "speedup_vs_naive_only": (ms["naive_only"] / ms["mixed"]) if "naive_only" in ms else None,
+        "prefix_expand_ms": expand_ms,
+        "expanded_prefix_bytes": C.expanded_prefix_bytes(shape),
+        "latent_prefix_bytes": C.latent_prefix_bytes(shape),
+        "kernel_ms": stage_ms,
+        "batch_threshold_nominal": C.batch_threshold(MFMA_BF16_PEAK, HBM_PEAK, S),
+    }
+
+    # ---- roofline of the dominant kernel
+    roofline = None
+    if stage_ms:
+        dom = max(stage_ms, key=stage_ms.get)
+        t = stage_ms[dom] * 1e-3
+        if dom == "prefix_attention":
+            # number of prefix splits actually planned is not visible here; the partial-output
+            # traffic is small, count one split
+            w = C.prefix_kernel_work(shape, 1)
+        elif dom == "absorb_attention":
+            w = C.suffix_kernel_work(shape, 0)
+        else:
+            w = None
+        if w is not None:
+            intensity = w["flops"] / w["bytes"]
+            ridge = MFMA_BF16_PEAK / HBM_PEAK
+            if intensity < ridge:
+                roofline = {"kernel": dom, "bound": "hbm", "achieved": w["bytes"] / t / 1e9,
+                            "peak": HBM_PEAK / 1e9, "unit": "GB/s"}
+            else:
+                roofline = {"kernel": dom, "bound": "mfma", "achieved": w["flops"] / t / 1e12,
+                            "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s"}
+            roofline["frac"] = roofline["achieved"] / roofline["peak"]
+            roofline["traffic"] = read_traffic(spec.name, dom)
+            roofline["algorithmic_bytes"] = w["bytes"]
+            roofline["algorithmic_flops"] = w["flops"]
+            roofline["kernel_ms"] = stage_ms[dom]
+            roofline["mfma_frac"] = w["flops"] / t / MFMA_BF16_PEAK
+            roofline["hbm_frac"] = w["bytes"] / t / HBM_PEAK
+    result["roofline"] = roofline
+
+    # ---- CPU baseline: the fp64 oracle as it stands, on a bounded sample of the same workload,
+    # which also serves as a parity check of the timed output
+    if not args.no_cpu_baseline:
+        import numpy as np
+        from oracle import mla_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            threads = os.cpu_count()
+        a = wl.as_float64()
+        n_req = args.cpu_sample_requests
+        if n_req <= 0:
+            # the cost is dominated by up-projecting every visible token once per head; keep the
+            # sample to a few requests so this leg stays within tens of seconds
+            n_req = 4 if L_s * H <= (1 << 20) else 2
+        reqs = sorted({0, B - 1} | set(range(0, B, max(1, B // n_req))))[:max(n_req, 1)]
+        reqs = [b for b in reqs if b < B]
+        pairs = [(b, h) for b in reqs for h in range(H)]
+        t0 = time.perf_counter()
+        ref, ref_lse = O.mla_decode_definition(**a, pairs=pairs)
+        cpu_s = time.perf_counter() - t0
+        mask = ~np.isnan(ref_lse)
+        err = np.abs(got[mask] - ref[mask])
+        rn = np.linalg.norm(ref[mask], axis=-1)
+        rel = np.linalg.norm(got[mask] - ref[mask], axis=-1) / np.maximum(rn, 1e-30)
+        fin = np.isfinite(ref_lse[mask])
+        result["cpu_baseline"] = {
+            "value": len(reqs) * S / cpu_s, "unit": "tokens/s", "cores": int(threads),
+            "kind": "oracle",
+            "sample": "%d of %d requests (all %d heads, whole prefix + suffix), fp64 definition "
+                      "oracle, %.1f s" % (len(reqs), B, H, cpu_s)}
+        result["parity_on_sample"] = {
+            "rows": int(mask.sum()), "max_abs_err": float(err.max()),
+            "max_row_rel_l2": float(rel[rn > 0].max()) if (rn > 0).any() else 0.0,
+            "max_lse_err": float(np.abs(got_lse[mask][fin] - ref_lse[mask][fin]).max())
+            if fin.any() else 0.0}
+    result["input_generation_s"] = gen_s
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

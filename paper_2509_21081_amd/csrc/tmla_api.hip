@@ -251,8 +251,28 @@ int typhoon_mla_decode(const tmla_dims* dims, int32_t mode, int32_t batch, int32
   a.sm_scale = dims->sm_scale; a.stream = (hipStream_t)stream;
 
   (void)hipGetLastError();
-  if (dims->dtype == TMLA_FP32) simple_decode<float>(p, a);
-  else simple_decode<bf16_t>(p, a);
+  if (dims->dtype == TMLA_FP32) {
+    simple_stage_naive<float>(p, a, 0, p.n_naive);
+    simple_stage_qabs<float>(p, a);
+    simple_stage_absorb<float>(p, a);
+    simple_stage_finalize<float>(p, a);
+  } else if (g_debug_flags & 1) {
+    simple_stage_naive<bf16_t>(p, a, 0, p.n_naive);
+    simple_stage_qabs<bf16_t>(p, a);
+    simple_stage_absorb<bf16_t>(p, a);
+    simple_stage_finalize<bf16_t>(p, a);
+  } else {
+    // bits 4..8 of the debug flags restrict the call to single stages (for per-kernel timing)
+    const int only = g_debug_flags & 0x1f0;
+    if (!only || (only & 0x10)) {
+      st = mfma_prefix_attention(p, a);
+      if (st != TMLA_OK) return st;
+    }
+    if (!only || (only & 0x20)) simple_stage_naive<bf16_t>(p, a, p.np_split, p.ns_chunks);
+    if (!only || (only & 0x40)) simple_stage_qabs<bf16_t>(p, a);
+    if (!only || (only & 0x80)) simple_stage_absorb<bf16_t>(p, a);
+    if (!only || (only & 0x100)) simple_stage_finalize<bf16_t>(p, a);
+  }
   return hipGetLastError() == hipSuccess ? TMLA_OK : TMLA_ERR_HIP;
 }
 

@@ -101,7 +101,14 @@ struct DecodeArgs {
 template <typename T>
 void simple_expand(int H, int64_t ntok, const T* c, int64_t c_stride, const T* r, int64_t r_stride,
                    const T* w_uk, const T* w_uv, T* k_out, T* v_out, hipStream_t stream);
-template <typename T> void simple_decode(const Plan& p, const DecodeArgs& a);
+template <typename T> void simple_stage_naive(const Plan& p, const DecodeArgs& a, int first_chunk,
+                                              int n_chunks);
+template <typename T> void simple_stage_qabs(const Plan& p, const DecodeArgs& a);
+template <typename T> void simple_stage_absorb(const Plan& p, const DecodeArgs& a);
+template <typename T> void simple_stage_finalize(const Plan& p, const DecodeArgs& a);
+
+// Matrix-core kernels (bf16).  Each returns a tmla_status.
+int mfma_prefix_attention(const Plan& p, const DecodeArgs& a);
 void launch_combine_lse(int num_partials, int64_t rows, int width, const float* po,
                         const float* pl, void* out, int out_dtype, float* lse_out,
                         hipStream_t stream);

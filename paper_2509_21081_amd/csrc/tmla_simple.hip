@@ -169,10 +169,10 @@ simple_naive_kernel(Plan p, const T* __restrict__ q, const T* __restrict__ pk,
                     const T* __restrict__ pv, const T* __restrict__ sk, const T* __restrict__ sv,
                     const int32_t* __restrict__ block_table, const int32_t* __restrict__ lens,
                     int max_blocks, int block_size, int64_t pool_tokens, float scale,
-                    float* __restrict__ naive_o, float* __restrict__ naive_lse) {
+                    float* __restrict__ naive_o, float* __restrict__ naive_lse, int first_chunk) {
   __shared__ float q_lds[D_QK];
   const int64_t row = blockIdx.x;
-  const int chunk = blockIdx.y;
+  const int chunk = first_chunk + blockIdx.y;
   const int h = (int)(row % p.H);
   const int s = (int)((row / p.H) % p.Sq);
   const int b = (int)(row / ((int64_t)p.H * p.Sq));
@@ -303,34 +303,46 @@ simple_finalize_kernel(Plan p, const float* __restrict__ naive_o,
 }
 
 template <typename T>
-void simple_decode(const Plan& p, const DecodeArgs& a) {
-  float* naive_o = (float*)(a.ws + p.off_naive_o);
-  float* naive_lse = (float*)(a.ws + p.off_naive_lse);
-  float* lat_o = (float*)(a.ws + p.off_lat_o);
-  float* lat_lse = (float*)(a.ws + p.off_lat_lse);
-  T* qabs = (T*)(a.ws + p.off_qabs);
+void simple_stage_naive(const Plan& p, const DecodeArgs& a, int first_chunk, int n_chunks) {
+  if (p.rows == 0 || n_chunks <= 0) return;
   const int64_t pool_tokens = (int64_t)a.num_blocks * a.block_size;
-  if (p.rows == 0) return;
-  if (p.n_naive > 0) {
-    hipLaunchKernelGGL(simple_naive_kernel<T>, dim3((unsigned)p.rows, p.n_naive), dim3(NT), 0,
-                       a.stream, p, (const T*)a.q, (const T*)a.prefix_k, (const T*)a.prefix_v,
-                       (const T*)a.suffix_k_pool, (const T*)a.suffix_v_pool, a.block_table,
-                       a.suffix_lens, a.max_blocks, a.block_size, pool_tokens, a.sm_scale, naive_o,
-                       naive_lse);
-  }
-  if (p.n_lat > 0) {
-    hipLaunchKernelGGL(simple_qabs_kernel<T>, dim3((unsigned)p.rows), dim3(256), 0, a.stream, p.H,
-                       (const T*)a.q, (const T*)a.w_uk, qabs);
-    hipLaunchKernelGGL(simple_absorb_kernel<T>, dim3((unsigned)p.rows, p.n_lat), dim3(NT), 0,
-                       a.stream, p, qabs, (const T*)a.prefix_ckv, (const T*)a.prefix_krope,
-                       (const T*)a.suffix_pool, a.block_table, a.suffix_lens, a.max_blocks,
-                       a.block_size, a.sm_scale, lat_o, lat_lse);
-  }
-  hipLaunchKernelGGL(simple_finalize_kernel<T>, dim3((unsigned)p.rows), dim3(NT), 0, a.stream, p,
-                     naive_o, naive_lse, lat_o, lat_lse, (const T*)a.w_uv, (T*)a.out, a.lse_out);
+  hipLaunchKernelGGL(simple_naive_kernel<T>, dim3((unsigned)p.rows, n_chunks), dim3(NT), 0,
+                     a.stream, p, (const T*)a.q, (const T*)a.prefix_k, (const T*)a.prefix_v,
+                     (const T*)a.suffix_k_pool, (const T*)a.suffix_v_pool, a.block_table,
+                     a.suffix_lens, a.max_blocks, a.block_size, pool_tokens, a.sm_scale,
+                     (float*)(a.ws + p.off_naive_o), (float*)(a.ws + p.off_naive_lse), first_chunk);
 }
-template void simple_decode<float>(const Plan&, const DecodeArgs&);
-template void simple_decode<bf16_t>(const Plan&, const DecodeArgs&);
+template <typename T>
+void simple_stage_qabs(const Plan& p, const DecodeArgs& a) {
+  if (p.rows == 0 || p.n_lat <= 0) return;
+  hipLaunchKernelGGL(simple_qabs_kernel<T>, dim3((unsigned)p.rows), dim3(256), 0, a.stream, p.H,
+                     (const T*)a.q, (const T*)a.w_uk, (T*)(a.ws + p.off_qabs));
+}
+template <typename T>
+void simple_stage_absorb(const Plan& p, const DecodeArgs& a) {
+  if (p.rows == 0 || p.n_lat <= 0) return;
+  hipLaunchKernelGGL(simple_absorb_kernel<T>, dim3((unsigned)p.rows, p.n_lat), dim3(NT), 0,
+                     a.stream, p, (const T*)(a.ws + p.off_qabs), (const T*)a.prefix_ckv,
+                     (const T*)a.prefix_krope, (const T*)a.suffix_pool, a.block_table,
+                     a.suffix_lens, a.max_blocks, a.block_size, a.sm_scale,
+                     (float*)(a.ws + p.off_lat_o), (float*)(a.ws + p.off_lat_lse));
+}
+template <typename T>
+void simple_stage_finalize(const Plan& p, const DecodeArgs& a) {
+  if (p.rows == 0) return;
+  hipLaunchKernelGGL(simple_finalize_kernel<T>, dim3((unsigned)p.rows), dim3(NT), 0, a.stream, p,
+                     (const float*)(a.ws + p.off_naive_o), (const float*)(a.ws + p.off_naive_lse),
+                     (const float*)(a.ws + p.off_lat_o), (const float*)(a.ws + p.off_lat_lse),
+                     (const T*)a.w_uv, (T*)a.out, a.lse_out);
+}
+#define TMLA_INSTANTIATE(T)                                                        \
+  template void simple_stage_naive<T>(const Plan&, const DecodeArgs&, int, int);   \
+  template void simple_stage_qabs<T>(const Plan&, const DecodeArgs&);              \
+  template void simple_stage_absorb<T>(const Plan&, const DecodeArgs&);            \
+  template void simple_stage_finalize<T>(const Plan&, const DecodeArgs&);
+TMLA_INSTANTIATE(float)
+TMLA_INSTANTIATE(bf16_t)
+#undef TMLA_INSTANTIATE
 
 // ---------------------------------------------------------------- stand-alone CombineLSE
 // One wavefront per row: lanes stride over the width, the max / sum over partials are per-lane

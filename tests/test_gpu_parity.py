@@ -28,6 +28,8 @@ SMALL_CASES = {
                    seed=25, q_gain=8.0),
     "h128_many_tiles": dict(batch=5, heads=128, q_len=1, prefix_len=300, suffix_min=40,
                             suffix_max=330, seed=26),
+    "batch_300": dict(batch=300, heads=16, q_len=1, prefix_len=200, suffix_min=0, suffix_max=40,
+                      seed=28),
     "wide_batch": dict(batch=70, heads=16, q_len=1, prefix_len=130, suffix_min=0, suffix_max=70,
                        seed=27),
 }
