@@ -150,6 +150,8 @@ int typhoon_mla_combine_lse(int32_t num_partials, int64_t rows, int32_t width,
 /*
  * Debug / tuning switches (process-wide, not thread-safe; default 0).
  *   bit 0: run the scalar reference kernels instead of the matrix-core kernels for bf16.
+ *   bits 1..3: scalar kernel for one stage only -- 2 query absorption, 4 absorb attention,
+ *     8 up-projection + combine (the other stages stay on the matrix cores).
  *   bits 4..8 (bf16 matrix-core path only): when any is set, decode launches only the selected
  *     stages, for per-kernel timing -- 0x10 naive prefix attention, 0x20 naive suffix attention,
  *     0x40 query absorption, 0x80 absorb attention, 0x100 up-projection + combine.  The output

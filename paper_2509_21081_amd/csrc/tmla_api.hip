@@ -70,6 +70,7 @@ int make_plan(const tmla_dims* dims, int mode, int B, int Sq, int Ls, int max_su
     if (mode == TMLA_MODE_ABSORB_ONLY && Ls > 0) {
       int chunk = env_int("TMLA_ABSORB_PREFIX_CHUNK", 0);
       if (chunk <= 0) chunk = std::max(512, round_up(ceil_div(Ls, std::max(1, ceil_div(2 * target, wgs))), 256));
+      chunk = std::max(chunk, ceil_div(Ls, MAX_CHUNKS));
       p->ap_chunk = round_up(std::min(chunk, round_up(Ls, TOK_BLK)), TOK_BLK);
       p->ap_chunks = ceil_div(Ls, p->ap_chunk);
     }
@@ -79,6 +80,7 @@ int make_plan(const tmla_dims* dims, int mode, int B, int Sq, int Ls, int max_su
         const int want = std::max(1, ceil_div(2 * target, wgs));  // chunks per request wanted
         chunk = std::max(256, ceil_div(max_suffix, want));
       }
+      chunk = std::max(chunk, ceil_div(max_suffix, MAX_CHUNKS));
       p->as_chunk = round_up(std::min(chunk, round_up(max_suffix, block_size)), block_size);
       p->as_chunks = ceil_div(max_suffix, p->as_chunk);
     }
@@ -269,9 +271,18 @@ int typhoon_mla_decode(const tmla_dims* dims, int32_t mode, int32_t batch, int32
       if (st != TMLA_OK) return st;
     }
     if (!only || (only & 0x20)) simple_stage_naive<bf16_t>(p, a, p.np_split, p.ns_chunks);
-    if (!only || (only & 0x40)) simple_stage_qabs<bf16_t>(p, a);
-    if (!only || (only & 0x80)) simple_stage_absorb<bf16_t>(p, a);
-    if (!only || (only & 0x100)) simple_stage_finalize<bf16_t>(p, a);
+    if (!only || (only & 0x40)) {
+      if (g_debug_flags & 2) simple_stage_qabs<bf16_t>(p, a);
+      else if ((st = mfma_query_absorb(p, a)) != TMLA_OK) return st;
+    }
+    if (!only || (only & 0x80)) {
+      if (g_debug_flags & 4) simple_stage_absorb<bf16_t>(p, a);
+      else if ((st = mfma_absorb_attention(p, a)) != TMLA_OK) return st;
+    }
+    if (!only || (only & 0x100)) {
+      if (g_debug_flags & 8) simple_stage_finalize<bf16_t>(p, a);
+      else if ((st = mfma_finalize(p, a)) != TMLA_OK) return st;
+    }
   }
   return hipGetLastError() == hipSuccess ? TMLA_OK : TMLA_ERR_HIP;
 }

@@ -109,6 +109,10 @@ template <typename T> void simple_stage_finalize(const Plan& p, const DecodeArgs
 
 // Matrix-core kernels (bf16).  Each returns a tmla_status.
 int mfma_prefix_attention(const Plan& p, const DecodeArgs& a);
+int mfma_query_absorb(const Plan& p, const DecodeArgs& a);
+int mfma_absorb_attention(const Plan& p, const DecodeArgs& a);
+int mfma_finalize(const Plan& p, const DecodeArgs& a);
+constexpr int MAX_CHUNKS = 32;  // per-request chunk bound for each of the latent prefix / suffix
 void launch_combine_lse(int num_partials, int64_t rows, int width, const float* po,
                         const float* pl, void* out, int out_dtype, float* lse_out,
                         hipStream_t stream);

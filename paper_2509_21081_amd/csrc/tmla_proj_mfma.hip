@@ -1,0 +1,235 @@
+// The two absorb projections on the matrix cores, each fused with its neighbour step:
+//   * query absorption  Q_abs = Q_nope W_UK  (paper Algorithm 1 step 5), plus the copy of the
+//     RoPE part, producing the 576-wide absorbed query rows the latent attention consumes;
+//   * up-projection O_A = O_lat W_UV^T (step 7) fused with the LSE combine (step 8): the latent
+//     split partials are merged on the fly while they are loaded as the MFMA operand, projected,
+//     then merged with the 128-wide naive partials and stored.
+// Both are per-head GEMMs with the queries on the MFMA column axis (transposed products, see
+// tmla_mfma.hpp), so all per-query softmax weights are per-lane scalars.
+#include "tmla_common.hpp"
+#include "tmla_mfma.hpp"
+
+namespace tmla {
+
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef short short8v __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
+
+// ------------------------------------------------------------------ step 5
+// grid (H, 4 latent quarters, ceil(M/128)); 4 wavefronts x 32 queries.  W_UK[h] is [128, 512]
+// with the contraction index (noPE dim) as the row, i.e. k-major: a [128 x 128] slice is staged
+// in LDS and read through the transposing LDS load to form the A operand (rows = latent columns).
+constexpr int QA_ROW_BYTES = 288;  // 256 + 32: 4 consecutive rows land on distinct banks
+
+__global__ void __launch_bounds__(256) qabs_kernel(const __bf16* __restrict__ q,
+                                                   const __bf16* __restrict__ w_uk,
+                                                   __bf16* __restrict__ qabs, int M, int H) {
+  __shared__ __attribute__((aligned(16))) char wt[128 * QA_ROW_BYTES];
+  const int h = blockIdx.x, lq = blockIdx.y, qsb = blockIdx.z;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, g = lane >> 5;
+  // stage W_UK[h][0:128][lq*128 : lq*128+128]: 128 rows x 16 chunks of 16 B
+  {
+    const __bf16* src = w_uk + ((size_t)h * D_N) * D_L + lq * 128;
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+      const int cidx = tid + 256 * i;
+      const int r = cidx >> 4, ch = cidx & 15;
+      *(bf16x8*)(wt + r * QA_ROW_BYTES + ch * 16) = *(const bf16x8*)(src + (size_t)r * D_L + ch * 8);
+    }
+  }
+  const int qi = (qsb * 4 + wave) * 32 + n;
+  const bool valid = qi < M;
+  const size_t row = (size_t)qi * H + h;
+  bf16x8 qf[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ks++) {
+    bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+    qf[ks] = valid ? *(const bf16x8*)(q + row * D_QK + 16 * ks + 8 * g) : z;
+  }
+  __syncthreads();
+  const int j16 = lane >> 4, r16 = lane & 15;
+  // transposing read: contraction row 16*ks + 8*g + 4*half + r/4, latent 32*mb + 16*(j%2) + 4*(r%4)
+  const int a_off = (8 * g + (r16 >> 2)) * QA_ROW_BYTES + (16 * (j16 & 1) + 4 * (r16 & 3)) * 2;
+  f32x16 acc[4];
+#pragma unroll
+  for (int mb = 0; mb < 4; mb++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) acc[mb][v] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 8; ks++) {
+#pragma unroll
+    for (int mb = 0; mb < 4; mb++) {
+      const char* src = wt + a_off + (16 * ks) * QA_ROW_BYTES + 64 * mb;
+      const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(src));
+      const short4v hi =
+          __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(src + 4 * QA_ROW_BYTES));
+      const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      acc[mb] = mfma32(__builtin_bit_cast(bf16x8, both), qf[ks], acc[mb]);
+    }
+  }
+  if (valid) {
+    __bf16* dst = qabs + row * D_ROW + lq * 128;
+#pragma unroll
+    for (int mb = 0; mb < 4; mb++)
+#pragma unroll
+      for (int v4 = 0; v4 < 4; v4++) {
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; e++) w[e] = (__bf16)acc[mb][4 * v4 + e];
+        *(bf16x4*)(dst + 32 * mb + 8 * v4 + 4 * g) = w;
+      }
+  }
+  if (lq == 0) {  // RoPE part: verbatim copy, 128 queries x 8 chunks
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int cidx = tid + 256 * i;
+      const int qq = qsb * 128 + (cidx >> 3), ch = cidx & 7;
+      if (qq < M) {
+        const size_t rr = (size_t)qq * H + h;
+        *(bf16x8*)(qabs + rr * D_ROW + D_L + ch * 8) = *(const bf16x8*)(q + rr * D_QK + D_N + ch * 8);
+      }
+    }
+  }
+}
+
+int mfma_query_absorb(const Plan& p, const DecodeArgs& d) {
+  if (p.n_lat <= 0 || p.rows == 0) return TMLA_OK;
+  const int M = p.B * p.Sq;
+  dim3 grid(p.H, 4, (M + 127) / 128);
+  hipLaunchKernelGGL(qabs_kernel, grid, dim3(256), 0, d.stream, (const __bf16*)d.q,
+                     (const __bf16*)d.w_uk, (__bf16*)(d.ws + p.off_qabs), M, p.H);
+  return TMLA_OK;
+}
+
+// ------------------------------------------------------------------ steps 7 + 8
+// grid (H, ceil(M/128)); a wavefront owns 32 queries of one head.
+constexpr int FIN_MAX_LAT = 64;  // latent partials per row supported by the weight table in LDS
+
+struct FinalizeArgs {
+  const float* naive_o; const float* naive_lse; const float* lat_o; const float* lat_lse;
+  const __bf16* w_uv; __bf16* out; float* lse_out;
+  int M, H, n_naive, n_lat;
+  int64_t rows;
+};
+
+__global__ void __launch_bounds__(256) finalize_kernel(FinalizeArgs a) {
+  __shared__ float wtab[4][FIN_MAX_LAT][32];   // normalised merge weight of each latent partial
+  const int h = blockIdx.x, qsb = blockIdx.y;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, g = lane >> 5;
+  const int qi = (qsb * 4 + wave) * 32 + n;
+  const bool valid = qi < a.M;
+  const size_t row = valid ? (size_t)qi * a.H + h : 0;
+
+  f32x16 acc[4];
+#pragma unroll
+  for (int mb = 0; mb < 4; mb++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) acc[mb][v] = 0.f;
+  float l_a = -INFINITY;
+  if (a.n_lat > 0) {
+    float mx = -INFINITY;
+    for (int i = 0; i < a.n_lat; i++) mx = fmaxf(mx, a.lat_lse[(size_t)i * a.rows + row]);
+    float z = 0.f;
+    if (mx > -INFINITY)
+      for (int i = 0; i < a.n_lat; i++) z += __expf(a.lat_lse[(size_t)i * a.rows + row] - mx);
+    const float inv = (z > 0.f && valid) ? 1.f / z : 0.f;
+    if (g == 0)
+      for (int i = 0; i < a.n_lat; i++)
+        wtab[wave][i][n] = (inv > 0.f) ? __expf(a.lat_lse[(size_t)i * a.rows + row] - mx) * inv : 0.f;
+    if (z > 0.f && valid) l_a = mx + __logf(z);
+    // wavefront-local table: the writes above are complete before the reads below because a
+    // wavefront executes its LDS instructions in order
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+    __builtin_amdgcn_wave_barrier();
+
+    const __bf16* wp = a.w_uv + ((size_t)h * D_V + n) * D_L + 8 * g;
+    const float* lp = a.lat_o + row * D_L + 8 * g;
+    for (int ks = 0; ks < 32; ks++) {
+      float m8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int i = 0; i < a.n_lat; i++) {
+        const float w = wtab[wave][i][n];
+        if (w > 0.f) {
+          const float4 x0 = *(const float4*)(lp + (size_t)i * a.rows * D_L + 16 * ks);
+          const float4 x1 = *(const float4*)(lp + (size_t)i * a.rows * D_L + 16 * ks + 4);
+          m8[0] += w * x0.x; m8[1] += w * x0.y; m8[2] += w * x0.z; m8[3] += w * x0.w;
+          m8[4] += w * x1.x; m8[5] += w * x1.y; m8[6] += w * x1.z; m8[7] += w * x1.w;
+        }
+      }
+      bf16x8 bfrag;
+#pragma unroll
+      for (int e = 0; e < 8; e++) bfrag[e] = (__bf16)m8[e];
+#pragma unroll
+      for (int mb = 0; mb < 4; mb++) {
+        const bf16x8 afrag = *(const bf16x8*)(wp + (size_t)(32 * mb) * D_L + 16 * ks);
+        acc[mb] = mfma32(afrag, bfrag, acc[mb]);
+      }
+    }
+  }
+  if (!valid) return;
+  // merge O_A (LSE l_a) with the naive partials
+  float m2 = l_a;
+  for (int i = 0; i < a.n_naive; i++) m2 = fmaxf(m2, a.naive_lse[(size_t)i * a.rows + row]);
+  __bf16* dst = a.out + row * D_V;
+  if (m2 == -INFINITY) {
+#pragma unroll
+    for (int mb = 0; mb < 4; mb++)
+#pragma unroll
+      for (int v4 = 0; v4 < 4; v4++) {
+        bf16x4 w = {0, 0, 0, 0};
+        *(bf16x4*)(dst + 32 * mb + 8 * v4 + 4 * g) = w;
+      }
+    if (a.lse_out && g == 0) a.lse_out[row] = -INFINITY;
+    return;
+  }
+  const float w_a = (l_a > -INFINITY) ? __expf(l_a - m2) : 0.f;
+  float z2 = w_a;
+#pragma unroll
+  for (int mb = 0; mb < 4; mb++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) acc[mb][v] *= w_a;
+  for (int i = 0; i < a.n_naive; i++) {
+    const float li = a.naive_lse[(size_t)i * a.rows + row];
+    if (li == -INFINITY) continue;
+    const float w = __expf(li - m2);
+    z2 += w;
+    const float* src = a.naive_o + ((size_t)i * a.rows + row) * D_V + 4 * g;
+#pragma unroll
+    for (int mb = 0; mb < 4; mb++)
+#pragma unroll
+      for (int v4 = 0; v4 < 4; v4++) {
+        const float4 x = *(const float4*)(src + 32 * mb + 8 * v4);
+        acc[mb][4 * v4] += w * x.x; acc[mb][4 * v4 + 1] += w * x.y;
+        acc[mb][4 * v4 + 2] += w * x.z; acc[mb][4 * v4 + 3] += w * x.w;
+      }
+  }
+  const float inv2 = 1.f / z2;
+#pragma unroll
+  for (int mb = 0; mb < 4; mb++)
+#pragma unroll
+    for (int v4 = 0; v4 < 4; v4++) {
+      bf16x4 w;
+#pragma unroll
+      for (int e = 0; e < 4; e++) w[e] = (__bf16)(acc[mb][4 * v4 + e] * inv2);
+      *(bf16x4*)(dst + 32 * mb + 8 * v4 + 4 * g) = w;
+    }
+  if (a.lse_out && g == 0) a.lse_out[row] = m2 + __logf(z2);
+}
+
+int mfma_finalize(const Plan& p, const DecodeArgs& d) {
+  if (p.rows == 0) return TMLA_OK;
+  if (p.n_lat > FIN_MAX_LAT) return TMLA_ERR_UNSUPPORTED;
+  FinalizeArgs a;
+  a.naive_o = (const float*)(d.ws + p.off_naive_o);
+  a.naive_lse = (const float*)(d.ws + p.off_naive_lse);
+  a.lat_o = (const float*)(d.ws + p.off_lat_o);
+  a.lat_lse = (const float*)(d.ws + p.off_lat_lse);
+  a.w_uv = (const __bf16*)d.w_uv;
+  a.out = (__bf16*)d.out;
+  a.lse_out = d.lse_out;
+  a.M = p.B * p.Sq; a.H = p.H; a.n_naive = p.n_naive; a.n_lat = p.n_lat; a.rows = p.rows;
+  dim3 grid(p.H, (a.M + 127) / 128);
+  hipLaunchKernelGGL(finalize_kernel, grid, dim3(256), 0, d.stream, a);
+  return TMLA_OK;
+}
+
+}  // namespace tmla
