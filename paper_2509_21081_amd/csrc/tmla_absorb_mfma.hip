@@ -17,14 +17,16 @@
 //   NQB = 1: 32 query rows (H = 16 with S_q <= 2), four wavefronts own 128 latent columns each;
 //            the scores are recomputed per wavefront, which the HBM-bound small-H case affords.
 #include <cstdlib>
+#include <type_traits>
+#include <utility>
 
 #include "tmla_common.hpp"
+#include "tmla_lds_asm.hpp"
 #include "tmla_mfma.hpp"
 
 namespace tmla {
 
-typedef short short4v __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
+constexpr int AB_CHUNKS = 72;  // 16-byte chunks per 576-wide cache row
 
 struct AbsorbArgs {
   const __bf16* qabs;        // [rows, 576]
@@ -38,15 +40,30 @@ struct AbsorbArgs {
   int Sq, H, R, Ls, ap_chunks, ap_chunk, as_chunk, max_blocks, block_size;
   int64_t rows;
   float c;                   // sm_scale * log2(e)
+  int dbg;
 };
 
+template <int... I, typename F>
+__device__ inline void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ inline void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
 constexpr int AB_ROW_BYTES = 1184;                 // 1152 + 32: see bank notes below
-constexpr int AB_TILE_BYTES = 32 * AB_ROW_BYTES;   // 37888
-constexpr int AB_LDS_BYTES = 2 * AB_TILE_BYTES;    // double buffer
-constexpr int AB_CHUNKS = 72;                      // 16-byte chunks per cache row
+constexpr int AB_ROW_SLOTS = AB_ROW_BYTES / 16;    // 74 sixteen-byte slots, the last two unused
+constexpr int AB_TILE_BYTES = 32 * AB_ROW_BYTES;   // 37888 = 37 x 1 KiB
+constexpr int AB_TILE_DMAS = AB_TILE_BYTES / 1024; // 37 wavefront-wide 1 KiB transfers per tile
+constexpr int AB_DMA_PER_WAVE = 10;                // ceil(37 / 4), surplus ones repeat the last
+constexpr int AB_NSLOT = 4;                        // tiles resident in LDS (3 in flight + 1 in use)
+constexpr int AB_LDS_BYTES = AB_NSLOT * AB_TILE_BYTES;
 // LDS tile: row r (token) at r * 1184; its 16-byte chunk c is stored at chunk slot
 // c ^ ((r >> 2) & 1).  The 32-byte row skew keeps the transposing reads (4 rows x 32 B per
 // 16 lanes) on distinct banks, the chunk swizzle separates rows r and r + 4 for the 16-byte reads.
+// Rows past the end of the chunk are filled from the last valid row (their scores are masked, so
+// they only have to be finite).
 
 template <int NQB>
 __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
@@ -93,51 +110,59 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
     }
   }
 
-  // ---- tile loader: 32 rows x 72 chunks = 2304 chunks, 9 per thread
-  bf16x8 stg[9];
-  const int32_t* bt = a.block_table + (size_t)b * a.max_blocks;
-  auto issue_loads = [&](int tile) {
-    const int tok0 = t0 + tile * 32;
-    const __bf16* page = nullptr;
-    if (!is_prefix) {
-      const int blk = bt[tok0 / a.block_size];
-      page = a.pool + ((size_t)blk * a.block_size + tok0 % a.block_size) * D_ROW;
-    }
+  // the fragments must be resident before the streamed loads start, so that no wait on them
+  // (which would also drain the tile prefetch) is needed inside the loop
 #pragma unroll
-    for (int i = 0; i < 9; i++) {
-      const int cidx = tid + 256 * i;
-      const int r = cidx / AB_CHUNKS, ch = cidx - r * AB_CHUNKS;
-      const int tok = tok0 + r;
-      bf16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (tok < t1) {
-        const __bf16* src;
-        if (is_prefix)
-          src = (ch < 64) ? a.pc + (size_t)tok * D_L + ch * 8 : a.pr + (size_t)tok * D_R + (ch - 64) * 8;
-        else
-          src = page + (size_t)r * D_ROW + ch * 8;
-        v = *(const bf16x8*)src;
+  for (int ks = 0; ks < 36; ks += 4)
+    asm volatile("s_waitcnt vmcnt(0)"
+                 : "+v"(qf[ks]), "+v"(qf[ks + 1]), "+v"(qf[ks + 2]), "+v"(qf[ks + 3])::"memory");
+
+  // ---- tile streaming: global -> LDS, this wavefront moves transfers wave, wave+4, ...
+  const int32_t* bt = a.block_table + (size_t)b * a.max_blocks;
+  auto issue_tile = [&](int tile, auto prefix_tag) {
+    constexpr bool PREFIX = decltype(prefix_tag)::value;
+    const int tok0 = t0 + tile * 32;
+    const int last = t1 - 1 - tok0;      // last valid row of this tile (>= 0)
+    const char* page = nullptr;
+    if constexpr (!PREFIX) {
+      const int blk = scalar_load_i32(bt + tok0 / a.block_size);
+      page = (const char*)(a.pool + ((size_t)blk * a.block_size + tok0 % a.block_size) * D_ROW);
+    }
+    char* dst = smem + (tile % AB_NSLOT) * AB_TILE_BYTES;
+#pragma unroll
+    for (int k = 0; k < AB_DMA_PER_WAVE; k++) {
+      const int idx = min(wave + 4 * k, AB_TILE_DMAS - 1);
+      const int slot = idx * 64 + lane;
+      const int r = slot / AB_ROW_SLOTS, sl = slot - r * AB_ROW_SLOTS;
+      const int ch = min(sl, AB_CHUNKS - 1) ^ ((r >> 2) & 1);
+      const int rr = min(r, last);
+      const char* src;
+      if constexpr (PREFIX) {
+        const size_t tok = (size_t)(tok0 + rr);
+        const char* s_c = (const char*)a.pc + tok * (D_L * 2) + ch * 16;
+        const char* s_r = (const char*)a.pr + tok * (D_R * 2) + (ch - 64) * 16;
+        src = (ch < 64) ? s_c : s_r;
+      } else {
+        src = page + rr * (D_ROW * 2) + ch * 16;
       }
-      stg[i] = v;
+      dma16(src, dst + idx * 1024);
     }
   };
-  auto store_lds = [&](int tile) {
-    char* buf = smem + (tile & 1) * AB_TILE_BYTES;
-#pragma unroll
-    for (int i = 0; i < 9; i++) {
-      const int cidx = tid + 256 * i;
-      const int r = cidx / AB_CHUNKS, ch = cidx - r * AB_CHUNKS;
-      *(bf16x8*)(buf + r * AB_ROW_BYTES + ((ch ^ ((r >> 2) & 1)) << 4)) = stg[i];
-    }
+  auto issue = [&](int tile) {
+    if (is_prefix) issue_tile(tile, std::true_type{});
+    else issue_tile(tile, std::false_type{});
   };
 
-  // per-lane LDS offsets
+  // per-lane LDS byte offsets inside a tile
   //   S phase: row n, chunk 2*ks + g  ->  n*1184 + ((g ^ sw_n) * 16) + 32*ks
-  const int s_off = n * AB_ROW_BYTES + ((g ^ ((n >> 2) & 1)) << 4);
+  const uint32_t smem_base = lds_addr(smem);
+  const uint32_t s_off = n * AB_ROW_BYTES + ((g ^ ((n >> 2) & 1)) << 4);
   //   P V phase (transposing read, 16-lane groups j = lane/16, r = lane%16):
   //     token row 16*kk + 8*half + 4*g + r/4, latent 32*mb + 16*(j%2) + 4*(r%4)
   const int j16 = lane >> 4, r16 = lane & 15;
-  const int v_off = (4 * g + (r16 >> 2)) * AB_ROW_BYTES +
-                    ((2 * (j16 & 1) + (((r16 & 3) >> 1) ^ g)) << 4) + 8 * (r16 & 1);
+  const uint32_t v_off = (4 * g + (r16 >> 2)) * AB_ROW_BYTES +
+                         ((2 * (j16 & 1) + (((r16 & 3) >> 1) ^ g)) << 4) + 8 * (r16 & 1) +
+                         64 * (lp * MBW);
 
   f32x16 o[MBW];
 #pragma unroll
@@ -146,19 +171,44 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
     for (int v = 0; v < 16; v++) o[mb][v] = 0.f;
   float m = -INFINITY, l = 0.f;
 
-  issue_loads(0);
-  store_lds(0);
-  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < AB_NSLOT - 1; t++)
+    if (t < ntile) issue(t);
+
   for (int tile = 0; tile < ntile; tile++) {
-    if (tile + 1 < ntile) issue_loads(tile + 1);
-    const char* buf = smem + (tile & 1) * AB_TILE_BYTES;
+    // this wavefront's transfers of `tile` are complete once at most the transfers of the
+    // following (up to two) tiles remain in flight
+    const int ahead = ntile - 1 - tile;
+    if (ahead >= 2) vm_wait<2 * AB_DMA_PER_WAVE>();
+    else if (ahead == 1) vm_wait<AB_DMA_PER_WAVE>();
+    else vm_wait<0>();
+    raw_barrier();   // everyone's part of `tile` has landed; everyone is done with tile - 1
+    if (tile + AB_NSLOT - 1 < ntile && !(a.dbg & 2)) issue(tile + AB_NSLOT - 1);
+    if (a.dbg & 1) continue;
+
+    const uint32_t tbase = smem_base + (tile % AB_NSLOT) * AB_TILE_BYTES;
+    const uint32_t sa = tbase + s_off;
     f32x16 sacc;
 #pragma unroll
     for (int v = 0; v < 16; v++) sacc[v] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < 36; ks++) {
-      const bf16x8 cf = *(const bf16x8*)(buf + s_off + 32 * ks);
-      sacc = mfma32(cf, qf[ks], sacc);
+    {
+      bf16x8 f[2][4];
+      static_for<4>([&](auto j) { f[0][j] = lds_read_b128<32 * decltype(j)::value>(sa); });
+      static_for<9>([&](auto grp) {
+        constexpr int G = decltype(grp)::value;
+        constexpr int cur = G & 1, nxt = cur ^ 1;
+        if constexpr (G + 1 < 9) {
+          static_for<4>([&](auto j) {
+            f[nxt][j] = lds_read_b128<32 * (4 * (G + 1) + decltype(j)::value)>(sa);
+          });
+          lgkm_wait<4>(f[cur][0], f[cur][1], f[cur][2], f[cur][3]);
+        } else {
+          lgkm_wait<0>(f[cur][0], f[cur][1], f[cur][2], f[cur][3]);
+        }
+        static_for<4>([&](auto j) {
+          sacc = mfma32(f[cur][j], qf[4 * G + decltype(j)::value], sacc);
+        });
+      });
     }
     const int limit = min(32, vis_q - (t0 + tile * 32));
     bf16x8 p[2];
@@ -170,21 +220,40 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
 #pragma unroll
         for (int v = 0; v < 16; v++) o[mb][v] *= alpha;
     }
-#pragma unroll
-    for (int mb = 0; mb < MBW; mb++) {
-#pragma unroll
-      for (int kk = 0; kk < 2; kk++) {
-        const char* src = buf + v_off + (16 * kk) * AB_ROW_BYTES + 64 * (lp * MBW + mb);
-        const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(src));
-        const short4v hi =
-            __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(src + 8 * AB_ROW_BYTES));
-        typedef short short8v __attribute__((ext_vector_type(8)));
-        const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        o[mb] = mfma32(__builtin_bit_cast(bf16x8, both), p[kk], o[mb]);
-      }
+    {
+      // step st = 2*mb + kk; groups of 4 steps (8 transposing reads), double buffered
+      const uint32_t va = tbase + v_off;
+      constexpr int NSTEP = 2 * MBW, NGRP = NSTEP / 4;
+      short4v lo[2][4], hi[2][4];
+      static_for<4>([&](auto j) {
+        constexpr int st = decltype(j)::value;
+        constexpr int off = (16 * (st & 1)) * AB_ROW_BYTES + 64 * (st >> 1);
+        lo[0][st] = lds_read_tr16_b64<off>(va);
+        hi[0][st] = lds_read_tr16_b64<off + 8 * AB_ROW_BYTES>(va);
+      });
+      static_for<NGRP>([&](auto grp) {
+        constexpr int G = decltype(grp)::value;
+        constexpr int cur = G & 1, nxt = cur ^ 1;
+        if constexpr (G + 1 < NGRP) {
+          static_for<4>([&](auto j) {
+            constexpr int st = 4 * (G + 1) + decltype(j)::value;
+            constexpr int off = (16 * (st & 1)) * AB_ROW_BYTES + 64 * (st >> 1);
+            lo[nxt][decltype(j)::value] = lds_read_tr16_b64<off>(va);
+            hi[nxt][decltype(j)::value] = lds_read_tr16_b64<off + 8 * AB_ROW_BYTES>(va);
+          });
+          lgkm_wait<8>(lo[cur][0], lo[cur][1], lo[cur][2], lo[cur][3]);
+          lgkm_wait<8>(hi[cur][0], hi[cur][1], hi[cur][2], hi[cur][3]);
+        } else {
+          lgkm_wait<0>(lo[cur][0], lo[cur][1], lo[cur][2], lo[cur][3]);
+          lgkm_wait<0>(hi[cur][0], hi[cur][1], hi[cur][2], hi[cur][3]);
+        }
+        static_for<4>([&](auto j) {
+          constexpr int st = 4 * G + decltype(j)::value;
+          o[st >> 1] = mfma32(join_tr(lo[cur][decltype(j)::value], hi[cur][decltype(j)::value]),
+                              p[st & 1], o[st >> 1]);
+        });
+      });
     }
-    if (tile + 1 < ntile) store_lds(tile + 1);
-    __syncthreads();
   }
 
   const float lt = sum_halves(l);
@@ -221,6 +290,7 @@ int mfma_absorb_attention(const Plan& p, const DecodeArgs& d) {
   a.max_blocks = d.max_blocks; a.block_size = d.block_size;
   a.rows = p.rows;
   a.c = d.sm_scale * LOG2E;
+  a.dbg = getenv("TMLA_ABSORB_DBG") ? atoi(getenv("TMLA_ABSORB_DBG")) : 0;
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)absorb_attn_kernel<4>,

@@ -1,0 +1,92 @@
+// Hand-placed LDS traffic for the software-pipelined kernels.
+//
+// The kernels stream tiles from global memory straight into LDS (global_load_lds, no staging
+// registers) several tiles ahead.  The compiler cannot tell which LDS bytes an in-flight
+// global-to-LDS load will write, so before any LDS read it can see it waits for ALL of them,
+// which would serialise the prefetch.  The reads of streamed tiles are therefore issued through
+// inline assembly and the waits are placed by hand:
+//   * vm_wait<N>()      : at most N of this wavefront's global(-to-LDS) loads still in flight
+//   * lds_read_*<OFF>() : issue an LDS read (result NOT yet valid)
+//   * lgkm_wait<N>(x..) : at most N LDS reads still in flight; the operands are tied to the wait so
+//                         no consumer of those registers can be scheduled above it
+// Every statement carries a "memory" clobber so global-to-LDS loads and barriers keep their
+// program order relative to it.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tmla_mfma.hpp"
+
+namespace tmla {
+
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef short short8v __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) char* lds_char_ptr;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef __attribute__((address_space(1))) const void* glb_void_ptr;
+
+// 32-bit LDS byte address of a pointer into shared memory
+__device__ inline uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(lds_char_ptr)(p);
+}
+
+template <int OFF>
+__device__ inline bf16x8 lds_read_b128(uint32_t addr) {
+  bf16x8 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+// transposing 64-bit read (four 16-bit elements gathered across 16 lanes)
+template <int OFF>
+__device__ inline short4v lds_read_tr16_b64(uint32_t addr) {
+  short4v v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+
+template <int N>
+__device__ inline void vm_wait() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+template <int N>
+__device__ inline void lgkm_wait() {
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
+template <int N, typename A>
+__device__ inline void lgkm_wait(A& a) {
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(N) : "memory");
+}
+template <int N, typename A, typename B>
+__device__ inline void lgkm_wait(A& a, B& b) {
+  asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N) : "memory");
+}
+template <int N, typename A, typename B, typename C, typename D>
+__device__ inline void lgkm_wait(A& a, B& b, C& c, D& d) {
+  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N) : "memory");
+}
+
+// workgroup barrier without the memory fence __syncthreads() implies (the fence would drain the
+// prefetched global-to-LDS loads); callers wait for exactly what they need first
+__device__ inline void raw_barrier() {
+  asm volatile("s_barrier" ::: "memory");
+}
+
+// 64 lanes x 16 bytes from per-lane global addresses to 1 KiB of LDS at the wave-uniform `dst`
+__device__ inline void dma16(const void* src, void* dst) {
+  __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(lds_char_ptr)dst, 16, 0, 0);
+}
+
+// Scalar (SMEM) load of one int from a wave-uniform address.  A vector load here would have to be
+// waited for with vmcnt(0), draining the tile prefetch; the scalar cache is only read.
+__device__ inline int scalar_load_i32(const int32_t* p) {
+  int v;
+  asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(p) : "memory");
+  return v;
+}
+
+__device__ inline bf16x8 join_tr(short4v lo, short4v hi) {
+  const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, both);
+}
+
+}  // namespace tmla
