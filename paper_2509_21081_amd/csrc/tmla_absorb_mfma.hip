@@ -43,15 +43,6 @@ struct AbsorbArgs {
   int dbg;
 };
 
-template <int... I, typename F>
-__device__ inline void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
-  (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, typename F>
-__device__ inline void static_for(F&& f) {
-  static_for_impl(std::make_integer_sequence<int, N>{}, f);
-}
-
 constexpr int AB_ROW_BYTES = 1184;                 // 1152 + 32: see bank notes below
 constexpr int AB_ROW_SLOTS = AB_ROW_BYTES / 16;    // 74 sixteen-byte slots, the last two unused
 constexpr int AB_TILE_BYTES = 32 * AB_ROW_BYTES;   // 37888 = 37 x 1 KiB

@@ -15,6 +15,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 #include "tmla_mfma.hpp"
 
 namespace tmla {
@@ -24,6 +27,16 @@ typedef short short8v __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) char* lds_char_ptr;
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef __attribute__((address_space(1))) const void* glb_void_ptr;
+
+// compile-time unrolled loop: f(std::integral_constant<int, 0>{}), ..., f(<N-1>)
+template <int... I, typename F>
+__device__ inline void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ inline void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
 
 // 32-bit LDS byte address of a pointer into shared memory
 __device__ inline uint32_t lds_addr(const void* p) {

@@ -20,6 +20,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
+constexpr float RESCALE_TAU = 8.f;
 
 __device__ inline f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -51,15 +52,18 @@ __device__ inline int acc_row(int v, int g) { return 8 * (v >> 2) + 4 * g + (v &
 
 // Online-softmax update for one 32-token block and one 32-query column block.
 //   s      : S^T accumulator (raw dot products); on return holds nothing useful
-//   m, l   : running max (log2 domain, already scaled) and this lane's partial denominator
+//   m, l   : exponent reference (log2 domain, scaled; >= running max - RESCALE_TAU) and this
+//            lane's partial denominator relative to it
 //   c      : sm_scale * log2(e)
-//   limit  : rows with acc_row >= limit are masked out (pass 32 for a full block)
+//   limit  : rows with acc_row >= limit are masked out (pass 32 for a full block); with
+//            MASK = false the block is known to be full and no masking code is emitted
 //   p0, p1 : the probabilities as bf16 B operands for the two 16-token k-steps
 // Returns the factor by which the caller must rescale its output accumulators (1 if unchanged);
 // `rescale` is wave-uniform and tells whether any lane needs it.
+template <bool MASK = true>
 __device__ inline float softmax_block(f32x16& s, float& m, float& l, float c, int limit, int g,
                                       bf16x8& p0, bf16x8& p1, bool& rescale) {
-  if (limit < 32) {
+  if (MASK && limit < 32) {
 #pragma unroll
     for (int v = 0; v < 16; v++)
       if (acc_row(v, g) >= limit) s[v] = -INFINITY;
@@ -68,7 +72,11 @@ __device__ inline float softmax_block(f32x16& s, float& m, float& l, float c, in
 #pragma unroll
   for (int v = 1; v < 16; v++) mx = fmaxf(mx, s[v]);
   mx = max_halves(mx) * c;
-  const float m_new = fmaxf(m, mx);
+  // Lazy reference update: `m` is the exponent reference, not necessarily the running maximum.
+  // It only moves when the block maximum exceeds it by more than RESCALE_TAU (log2 units), so
+  // probabilities stay below 2^RESCALE_TAU and the costly rescale of the output accumulators
+  // becomes rare.  The result is unchanged: numerator and denominator share the reference.
+  const float m_new = (mx > m + RESCALE_TAU) ? mx : m;
   const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
   float alpha = 1.f;
   rescale = __builtin_amdgcn_ballot_w64(m_new > m) != 0;
