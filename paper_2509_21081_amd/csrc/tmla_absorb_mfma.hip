@@ -43,18 +43,22 @@ struct AbsorbArgs {
   int dbg;
 };
 
-constexpr int AB_ROW_BYTES = 1184;                 // 1152 + 32: see bank notes below
-constexpr int AB_ROW_SLOTS = AB_ROW_BYTES / 16;    // 74 sixteen-byte slots, the last two unused
-constexpr int AB_TILE_BYTES = 32 * AB_ROW_BYTES;   // 37888 = 37 x 1 KiB
-constexpr int AB_TILE_DMAS = AB_TILE_BYTES / 1024; // 37 wavefront-wide 1 KiB transfers per tile
-constexpr int AB_DMA_PER_WAVE = 10;                // ceil(37 / 4), surplus ones repeat the last
+// LDS tile of 32 tokens (37888 B):
+//   latent part: row r (token) at r * 1056, holding the 64 sixteen-byte chunks of its 512 latent
+//     columns; chunk c sits in slot c ^ ((r >> 2) & 1).  The 32-byte row skew keeps the
+//     transposing reads (4 rows x 32 B per 16 lanes) on distinct banks, the slot swizzle
+//     separates rows r and r + 4 for the 16-byte reads of the score product.
+//   rope part: 32 rows x 128 B behind it, chunk c of row r in slot c ^ (r & 7).
+// A tile is filled by 36 wavefront-wide 1 KiB transfers: one per latent row (the swizzle is
+// uniform per row) and four for the rope parts of eight rows each.  Rows past the end of the
+// chunk are filled from the last valid row: their scores are masked, so they only have to be
+// finite.
+constexpr int AB_ROW_BYTES = 1056;
+constexpr int AB_MAIN_BYTES = 32 * AB_ROW_BYTES;   // 33792
+constexpr int AB_TILE_BYTES = AB_MAIN_BYTES + 32 * 128;   // 37888
+constexpr int AB_DMA_PER_WAVE = 9;                 // 8 latent rows + 1 rope group per wavefront
 constexpr int AB_NSLOT = 4;                        // tiles resident in LDS (3 in flight + 1 in use)
 constexpr int AB_LDS_BYTES = AB_NSLOT * AB_TILE_BYTES;
-// LDS tile: row r (token) at r * 1184; its 16-byte chunk c is stored at chunk slot
-// c ^ ((r >> 2) & 1).  The 32-byte row skew keeps the transposing reads (4 rows x 32 B per
-// 16 lanes) on distinct banks, the chunk swizzle separates rows r and r + 4 for the 16-byte reads.
-// Rows past the end of the chunk are filled from the last valid row (their scores are masked, so
-// they only have to be finite).
 
 template <int NQB>
 __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
@@ -108,35 +112,41 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
     asm volatile("s_waitcnt vmcnt(0)"
                  : "+v"(qf[ks]), "+v"(qf[ks + 1]), "+v"(qf[ks + 2]), "+v"(qf[ks + 3])::"memory");
 
-  // ---- tile streaming: global -> LDS, this wavefront moves transfers wave, wave+4, ...
+  // ---- tile streaming: global -> LDS.  This wavefront moves latent rows wave, wave+4, ... and
+  // the rope parts of rows 8*wave .. 8*wave+7.  All row arithmetic is wave-uniform; the only
+  // per-lane terms are the two swizzled lane offsets and the rope lane's row / chunk.
   const int32_t* bt = a.block_table + (size_t)b * a.max_blocks;
+  const int lane_off0 = lane << 4, lane_off1 = (lane ^ 1) << 4;
+  const int rope_row = 8 * wave + (lane >> 3);
+  const int rope_ch = ((lane & 7) ^ ((lane >> 3) & 7)) << 4;
   auto issue_tile = [&](int tile, auto prefix_tag) {
     constexpr bool PREFIX = decltype(prefix_tag)::value;
     const int tok0 = t0 + tile * 32;
     const int last = t1 - 1 - tok0;      // last valid row of this tile (>= 0)
-    const char* page = nullptr;
-    if constexpr (!PREFIX) {
+    const char* base;                    // first latent row of the tile
+    if constexpr (PREFIX) {
+      base = (const char*)a.pc + (size_t)tok0 * (D_L * 2);
+    } else {
       const int blk = scalar_load_i32(bt + tok0 / a.block_size);
-      page = (const char*)(a.pool + ((size_t)blk * a.block_size + tok0 % a.block_size) * D_ROW);
+      base = (const char*)(a.pool + ((size_t)blk * a.block_size + tok0 % a.block_size) * D_ROW);
     }
+    constexpr int row_bytes = PREFIX ? D_L * 2 : D_ROW * 2;
     char* dst = smem + (tile % AB_NSLOT) * AB_TILE_BYTES;
 #pragma unroll
-    for (int k = 0; k < AB_DMA_PER_WAVE; k++) {
-      const int idx = min(wave + 4 * k, AB_TILE_DMAS - 1);
-      const int slot = idx * 64 + lane;
-      const int r = slot / AB_ROW_SLOTS, sl = slot - r * AB_ROW_SLOTS;
-      const int ch = min(sl, AB_CHUNKS - 1) ^ ((r >> 2) & 1);
+    for (int k = 0; k < 8; k++) {
+      const int r = wave + 4 * k;
       const int rr = min(r, last);
+      const int loff = ((r >> 2) & 1) ? lane_off1 : lane_off0;   // (r >> 2) & 1 == k & 1
+      dma16(base + (size_t)rr * row_bytes + loff, dst + r * AB_ROW_BYTES);
+    }
+    {
+      const int rr = min(rope_row, last);
       const char* src;
-      if constexpr (PREFIX) {
-        const size_t tok = (size_t)(tok0 + rr);
-        const char* s_c = (const char*)a.pc + tok * (D_L * 2) + ch * 16;
-        const char* s_r = (const char*)a.pr + tok * (D_R * 2) + (ch - 64) * 16;
-        src = (ch < 64) ? s_c : s_r;
-      } else {
-        src = page + rr * (D_ROW * 2) + ch * 16;
-      }
-      dma16(src, dst + idx * 1024);
+      if constexpr (PREFIX)
+        src = (const char*)a.pr + (size_t)(tok0 + rr) * (D_R * 2) + rope_ch;
+      else
+        src = base + (size_t)rr * row_bytes + D_L * 2 + rope_ch;
+      dma16(src, dst + AB_MAIN_BYTES + wave * 1024);
     }
   };
   auto issue = [&](int tile) {
@@ -145,10 +155,15 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
   };
 
   // per-lane LDS byte offsets inside a tile
-  //   S phase: row n, chunk 2*ks + g  ->  n*1184 + ((g ^ sw_n) * 16) + 32*ks
+  //   score product, latent k-steps ks < 32: row n, chunk 2*ks + g
+  //       -> n*1056 + ((g ^ sw_n) * 16) + 32*ks            (sw_n = (n >> 2) & 1)
+  //   rope k-steps ks = 32 + k: row n, chunk c = 2*k + g in slot c ^ (n & 7)
   const uint32_t smem_base = lds_addr(smem);
   const uint32_t s_off = n * AB_ROW_BYTES + ((g ^ ((n >> 2) & 1)) << 4);
-  //   P V phase (transposing read, 16-lane groups j = lane/16, r = lane%16):
+  uint32_t r_off[4];
+#pragma unroll
+  for (int k = 0; k < 4; k++) r_off[k] = AB_MAIN_BYTES + n * 128 + (((2 * k + g) ^ (n & 7)) << 4);
+  //   P V product (transposing read, 16-lane groups j = lane/16, r = lane%16):
   //     token row 16*kk + 8*half + 4*g + r/4, latent 32*mb + 16*(j%2) + 4*(r%4)
   const int j16 = lane >> 4, r16 = lane & 15;
   const uint32_t v_off = (4 * g + (r16 >> 2)) * AB_ROW_BYTES +
@@ -183,14 +198,20 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
 #pragma unroll
     for (int v = 0; v < 16; v++) sacc[v] = 0.f;
     {
+      // 9 groups of 4 k-steps; the last group is the rope part
       bf16x8 f[2][4];
       static_for<4>([&](auto j) { f[0][j] = lds_read_b128<32 * decltype(j)::value>(sa); });
       static_for<9>([&](auto grp) {
         constexpr int G = decltype(grp)::value;
         constexpr int cur = G & 1, nxt = cur ^ 1;
-        if constexpr (G + 1 < 9) {
+        if constexpr (G + 1 < 8) {
           static_for<4>([&](auto j) {
             f[nxt][j] = lds_read_b128<32 * (4 * (G + 1) + decltype(j)::value)>(sa);
+          });
+          lgkm_wait<4>(f[cur][0], f[cur][1], f[cur][2], f[cur][3]);
+        } else if constexpr (G + 1 == 8) {
+          static_for<4>([&](auto j) {
+            f[nxt][j] = lds_read_b128<0>(tbase + r_off[decltype(j)::value]);
           });
           lgkm_wait<4>(f[cur][0], f[cur][1], f[cur][2], f[cur][3]);
         } else {

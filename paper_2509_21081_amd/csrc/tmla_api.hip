@@ -151,10 +151,14 @@ static int expand_common(const tmla_dims* dims, int64_t ntok, const void* c, int
     simple_expand<float>(dims->num_heads, ntok, (const float*)c, c_stride, (const float*)r,
                          r_stride, (const float*)w_uk, (const float*)w_uv, (float*)k_out,
                          (float*)v_out, st);
-  } else {
+  } else if (g_debug_flags & 1) {
     simple_expand<bf16_t>(dims->num_heads, ntok, (const bf16_t*)c, c_stride, (const bf16_t*)r,
                           r_stride, (const bf16_t*)w_uk, (const bf16_t*)w_uv, (bf16_t*)k_out,
                           (bf16_t*)v_out, st);
+  } else {
+    const int rc = mfma_expand(dims->num_heads, ntok, c, c_stride, r, r_stride, w_uk, w_uv, k_out,
+                               v_out, st);
+    if (rc != TMLA_OK) return rc;
   }
   return hipGetLastError() == hipSuccess ? TMLA_OK : TMLA_ERR_HIP;
 }

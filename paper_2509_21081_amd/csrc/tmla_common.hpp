@@ -108,6 +108,9 @@ template <typename T> void simple_stage_absorb(const Plan& p, const DecodeArgs& 
 template <typename T> void simple_stage_finalize(const Plan& p, const DecodeArgs& a);
 
 // Matrix-core kernels (bf16).  Each returns a tmla_status.
+int mfma_expand(int H, int64_t ntok, const void* c, int64_t c_stride, const void* r,
+                int64_t r_stride, const void* w_uk, const void* w_uv, void* k_out, void* v_out,
+                hipStream_t stream);
 int mfma_prefix_attention(const Plan& p, const DecodeArgs& a);
 int mfma_query_absorb(const Plan& p, const DecodeArgs& a);
 int mfma_absorb_attention(const Plan& p, const DecodeArgs& a);

@@ -16,6 +16,7 @@
 //     softmaxes are merged through LDS at the end.  Used for small batches, the HBM-bound regime.
 // Split-K over the prefix comes on top (grid.z); each workgroup writes a normalised partial
 // output and its natural-log LSE for the combine step.
+#include <cstdio>
 #include <cstdlib>
 
 #include "tmla_common.hpp"
@@ -180,8 +181,8 @@ __global__ void __launch_bounds__(QS_WAVES * 64, 1) prefix_attn_query_split_kern
     const int newest = min(nblk - 1, i + QS_AHEAD - 1);   // newest block issued so far
     if (k_mover) qs_wait_pending<3>(newest - i);
     else qs_wait_pending<2>(newest - i);
-    raw_barrier();
-    if (i + QS_AHEAD < nblk) issue(i + QS_AHEAD);
+    if (!(a.dbg & 16)) raw_barrier();
+    if (i + QS_AHEAD < nblk && !(a.dbg & 8)) issue(i + QS_AHEAD);
   };
   auto blk_addr = [&](int i) { return smem_addr + (i % QS_NSLOT) * QS_BLOCK_BYTES; };
   auto rescale_o = [&](float alpha, bool resc) {
@@ -195,31 +196,58 @@ __global__ void __launch_bounds__(QS_WAVES * 64, 1) prefix_attn_query_split_kern
 
   // One pipeline phase for full block i: its scores (matrix core), then its softmax (vector
   // ALU) side by side with P V of block i-1 (matrix core), which uses the previous phase's P.
-  auto phase = [&](int i, bf16x8 (&p_out)[2], const bf16x8 (&p_in)[2]) {
-    sync_and_refill(i);
-    f32x16 s = qs_scores(blk_addr(i), qf);
-    bool resc;
-    const float alpha = softmax_block<false>(s, m, l, a.c, 32, g, p_out[0], p_out[1], resc);
-    if (i > 0) qs_pv(blk_addr(i - 1), p_in, o);
-    rescale_o(alpha, resc);
-  };
-
+  // The two wavefronts that share a SIMD (w and w+4) run the same work in a different order so
+  // that one is on the matrix core while the other is on the vector ALU:
+  //   wavefronts 0-3, period i:  scores(i)     -> softmax(i)   -> P V(i-1)
+  //   wavefronts 4-7, period i:  softmax(i-1)  -> scores(i)    -> P V(i-1)
+  // Both read K of block i and V of block i-1 in period i, so the ring bookkeeping is the same,
+  // and both call sync_and_refill exactly once per block.
+  const int tail_limit = a.Ls - (tb0 + nblk - 1) * TOK_BLK;   // valid tokens of a partial tail
   bf16x8 p_a[2], p_b[2];
-  for (int i = 0; i < nfull; i += 2) {
-    phase(i, p_a, p_b);
-    if (i + 1 < nfull) phase(i + 1, p_b, p_a);
-  }
-  if (nfull > 0) {
-    if (nfull & 1) qs_pv(blk_addr(nfull - 1), p_a, o);
-    else qs_pv(blk_addr(nfull - 1), p_b, o);
+  bool resc;
+  const bool group_a = a.dbg == 1 ? (wave & 1) == 0 : a.dbg == 2 ? ((wave >> 1) & 1) == 0
+                       : a.dbg == 3 ? true : wave < 4;
+  if (group_a) {
+    auto phase = [&](int i, bf16x8 (&p_out)[2], const bf16x8 (&p_in)[2]) {
+      sync_and_refill(i);
+      f32x16 s = qs_scores(blk_addr(i), qf);
+      const float alpha = softmax_block<false>(s, m, l, a.c, 32, g, p_out[0], p_out[1], resc);
+      if (i > 0) qs_pv(blk_addr(i - 1), p_in, o);
+      rescale_o(alpha, resc);
+    };
+    for (int i = 0; i < nfull; i += 2) {
+      phase(i, p_a, p_b);
+      if (i + 1 < nfull) phase(i + 1, p_b, p_a);
+    }
+    if (has_tail) sync_and_refill(nblk - 1);
+    if (nfull > 0) {
+      if (nfull & 1) qs_pv(blk_addr(nfull - 1), p_a, o);
+      else qs_pv(blk_addr(nfull - 1), p_b, o);
+    }
+  } else {
+    f32x16 s_hold;
+    if (nfull > 0) {
+      sync_and_refill(0);
+      s_hold = qs_scores(blk_addr(0), qf);
+    }
+    for (int i = 1; i < nfull; i++) {
+      sync_and_refill(i);
+      const float alpha = softmax_block<false>(s_hold, m, l, a.c, 32, g, p_a[0], p_a[1], resc);
+      rescale_o(alpha, resc);
+      s_hold = qs_scores(blk_addr(i), qf);
+      qs_pv(blk_addr(i - 1), p_a, o);
+    }
+    if (has_tail) sync_and_refill(nblk - 1);
+    if (nfull > 0) {
+      const float alpha = softmax_block<false>(s_hold, m, l, a.c, 32, g, p_a[0], p_a[1], resc);
+      rescale_o(alpha, resc);
+      qs_pv(blk_addr(nfull - 1), p_a, o);
+    }
   }
   if (has_tail) {   // partial last block of the prefix: plain masked pass
     const int i = nblk - 1;
-    sync_and_refill(i);
     f32x16 s = qs_scores(blk_addr(i), qf);
-    bool resc;
-    const float alpha = softmax_block<true>(s, m, l, a.c, a.Ls - (tb0 + i) * TOK_BLK, g, p_a[0],
-                                            p_a[1], resc);
+    const float alpha = softmax_block<true>(s, m, l, a.c, tail_limit, g, p_a[0], p_a[1], resc);
     rescale_o(alpha, resc);
     qs_pv(blk_addr(i), p_a, o);
   }

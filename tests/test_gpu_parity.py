@@ -60,9 +60,12 @@ def test_small_cases(case, dtype, mode, flags, gpu_device):
                      logit_gain=wl.spec.q_gain)
 
 
+@pytest.mark.parametrize("flags", [0, 1], ids=["mfma", "scalar"])
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
-@pytest.mark.parametrize("ntok", [1, 31, 64, 100])
-def test_expand_prefix_matches_definition(dtype, ntok, gpu_device):
+@pytest.mark.parametrize("ntok", [1, 31, 64, 100, 300])
+def test_expand_prefix_matches_definition(dtype, ntok, flags, gpu_device):
+    if dtype == "fp32" and flags == 1:
+        pytest.skip("fp32 always runs the scalar kernels")
     wl = W.make_workload(W.small_spec(dtype=dtype, batch=1, heads=16, prefix_len=ntok,
                                       suffix_min=1, suffix_max=1, seed=40 + ntok))
     a = wl.as_float64()
@@ -70,9 +73,13 @@ def test_expand_prefix_matches_definition(dtype, ntok, gpu_device):
                                               a["w_uv"])
     d = wl.to(gpu_device)
     dims = Hh.dims_of(wl)
-    print(f"expand dtype={dtype} ntok={ntok}", flush=True)
-    pk, pv = T.typhoon_mla_expand_prefix(dims, d.prefix_ckv, d.prefix_krope, d.w_uk, d.w_uv)
-    torch.cuda.synchronize()
+    print(f"expand dtype={dtype} ntok={ntok} flags={flags}", flush=True)
+    old = T.typhoon_mla_set_debug_flags(flags)
+    try:
+        pk, pv = T.typhoon_mla_expand_prefix(dims, d.prefix_ckv, d.prefix_krope, d.w_uk, d.w_uv)
+        torch.cuda.synchronize()
+    finally:
+        T.typhoon_mla_set_debug_flags(old)
     K, V = Hh.unpack_expanded(pk, pv, 16, ntok, dtype)
     rt = 2.0 ** -8 if dtype == "bf16" else 1e-5      # one bf16 rounding of an fp32 accumulation
     np.testing.assert_allclose(K, k_ref, rtol=rt, atol=1e-3 if dtype == "bf16" else 1e-6)
