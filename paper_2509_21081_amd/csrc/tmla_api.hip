@@ -51,9 +51,11 @@ int make_plan(const tmla_dims* dims, int mode, int B, int Sq, int Ls, int max_su
 
   if (Ls > 0 && mode != TMLA_MODE_ABSORB_ONLY) {
     // naive prefix pass: one workgroup owns a head and a block of up to 256 queries
-    const int wgs = std::max(1, H * ceil_div(M, 256));
+    // (64 when the batch is small and the token-split kernel runs); one workgroup fits per
+    // compute unit, so the prefix is split until the grid covers the chip once
+    const int wgs = std::max(1, H * (M > 128 ? ceil_div(M, 256) : ceil_div(M, 64)));
     int splits = env_int("TMLA_PREFIX_SPLITS", 0);
-    if (splits <= 0) splits = ceil_div(target, wgs);
+    if (splits <= 0) splits = std::max(1, NUM_CU / wgs);
     splits = std::max(1, std::min(splits, ceil_div(Ls, 128)));
     p->p_chunk = round_up(ceil_div(Ls, splits), TOK_BLK);
     p->np_split = ceil_div(Ls, p->p_chunk);

@@ -102,7 +102,10 @@ int mfma_query_absorb(const Plan& p, const DecodeArgs& d) {
 }
 
 // ------------------------------------------------------------------ steps 7 + 8
-// grid (H, ceil(M/128)); a wavefront owns 32 queries of one head.
+// grid (H, ceil(M/32)); the four wavefronts of a workgroup share 32 queries of one head and split
+// the 512-wide contraction of the up-projection in four; their partial products are summed
+// through LDS, after which wavefront w finishes value columns [32w, 32w+32): merge with the naive
+// partials, normalise, store.
 constexpr int FIN_MAX_LAT = 64;  // latent partials per row supported by the weight table in LDS
 
 struct FinalizeArgs {
@@ -113,19 +116,18 @@ struct FinalizeArgs {
 };
 
 __global__ void __launch_bounds__(256) finalize_kernel(FinalizeArgs a) {
-  __shared__ float wtab[4][FIN_MAX_LAT][32];   // normalised merge weight of each latent partial
-  const int h = blockIdx.x, qsb = blockIdx.y;
+  __shared__ float wtab[FIN_MAX_LAT][32];    // normalised merge weight of each latent partial
+  __shared__ float red[4][4][16][64];        // [wavefront][value block][acc register][lane]
+  const int h = blockIdx.x, qb = blockIdx.y;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, g = lane >> 5;
-  const int qi = (qsb * 4 + wave) * 32 + n;
+  const int qi = qb * 32 + n;
   const bool valid = qi < a.M;
   const size_t row = valid ? (size_t)qi * a.H + h : 0;
 
-  f32x16 acc[4];
-#pragma unroll
-  for (int mb = 0; mb < 4; mb++)
-#pragma unroll
-    for (int v = 0; v < 16; v++) acc[mb][v] = 0.f;
   float l_a = -INFINITY;
+  float oa[16];   // this wavefront's 32 value columns of O_A after the cross-wavefront sum
+#pragma unroll
+  for (int v = 0; v < 16; v++) oa[v] = 0.f;
   if (a.n_lat > 0) {
     float mx = -INFINITY;
     for (int i = 0; i < a.n_lat; i++) mx = fmaxf(mx, a.lat_lse[(size_t)i * a.rows + row]);
@@ -133,21 +135,24 @@ __global__ void __launch_bounds__(256) finalize_kernel(FinalizeArgs a) {
     if (mx > -INFINITY)
       for (int i = 0; i < a.n_lat; i++) z += __expf(a.lat_lse[(size_t)i * a.rows + row] - mx);
     const float inv = (z > 0.f && valid) ? 1.f / z : 0.f;
-    if (g == 0)
+    // every wavefront computes the same weights; wavefront 0 publishes them
+    if (wave == 0 && g == 0)
       for (int i = 0; i < a.n_lat; i++)
-        wtab[wave][i][n] = (inv > 0.f) ? __expf(a.lat_lse[(size_t)i * a.rows + row] - mx) * inv : 0.f;
+        wtab[i][n] = (inv > 0.f) ? __expf(a.lat_lse[(size_t)i * a.rows + row] - mx) * inv : 0.f;
     if (z > 0.f && valid) l_a = mx + __logf(z);
-    // wavefront-local table: the writes above are complete before the reads below because a
-    // wavefront executes its LDS instructions in order
-    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
-    __builtin_amdgcn_wave_barrier();
+    __syncthreads();
 
-    const __bf16* wp = a.w_uv + ((size_t)h * D_V + n) * D_L + 8 * g;
-    const float* lp = a.lat_o + row * D_L + 8 * g;
-    for (int ks = 0; ks < 32; ks++) {
+    f32x16 acc[4];
+#pragma unroll
+    for (int mb = 0; mb < 4; mb++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[mb][v] = 0.f;
+    const __bf16* wp = a.w_uv + ((size_t)h * D_V + n) * D_L + 8 * g + 128 * wave;
+    const float* lp = a.lat_o + row * D_L + 8 * g + 128 * wave;
+    for (int ks = 0; ks < 8; ks++) {
       float m8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       for (int i = 0; i < a.n_lat; i++) {
-        const float w = wtab[wave][i][n];
+        const float w = wtab[i][n];
         if (w > 0.f) {
           const float4 x0 = *(const float4*)(lp + (size_t)i * a.rows * D_L + 16 * ks);
           const float4 x1 = *(const float4*)(lp + (size_t)i * a.rows * D_L + 16 * ks + 4);
@@ -164,55 +169,56 @@ __global__ void __launch_bounds__(256) finalize_kernel(FinalizeArgs a) {
         acc[mb] = mfma32(afrag, bfrag, acc[mb]);
       }
     }
-  }
-  if (!valid) return;
-  // merge O_A (LSE l_a) with the naive partials
-  float m2 = l_a;
-  for (int i = 0; i < a.n_naive; i++) m2 = fmaxf(m2, a.naive_lse[(size_t)i * a.rows + row]);
-  __bf16* dst = a.out + row * D_V;
-  if (m2 == -INFINITY) {
 #pragma unroll
     for (int mb = 0; mb < 4; mb++)
 #pragma unroll
-      for (int v4 = 0; v4 < 4; v4++) {
-        bf16x4 w = {0, 0, 0, 0};
-        *(bf16x4*)(dst + 32 * mb + 8 * v4 + 4 * g) = w;
-      }
-    if (a.lse_out && g == 0) a.lse_out[row] = -INFINITY;
+      for (int v = 0; v < 16; v++) red[wave][mb][v][lane] = acc[mb][v];
+    __syncthreads();
+#pragma unroll
+    for (int v = 0; v < 16; v++)
+      oa[v] = red[0][wave][v][lane] + red[1][wave][v][lane] + red[2][wave][v][lane] +
+              red[3][wave][v][lane];
+  }
+  if (!valid) return;
+  // merge O_A (LSE l_a) with the naive partials; this wavefront owns value block `wave`
+  float m2 = l_a;
+  for (int i = 0; i < a.n_naive; i++) m2 = fmaxf(m2, a.naive_lse[(size_t)i * a.rows + row]);
+  __bf16* dst = a.out + row * D_V + 32 * wave + 4 * g;
+  if (m2 == -INFINITY) {
+#pragma unroll
+    for (int v4 = 0; v4 < 4; v4++) {
+      bf16x4 w = {0, 0, 0, 0};
+      *(bf16x4*)(dst + 8 * v4) = w;
+    }
+    if (a.lse_out && wave == 0 && g == 0) a.lse_out[row] = -INFINITY;
     return;
   }
   const float w_a = (l_a > -INFINITY) ? __expf(l_a - m2) : 0.f;
   float z2 = w_a;
 #pragma unroll
-  for (int mb = 0; mb < 4; mb++)
-#pragma unroll
-    for (int v = 0; v < 16; v++) acc[mb][v] *= w_a;
+  for (int v = 0; v < 16; v++) oa[v] *= w_a;
   for (int i = 0; i < a.n_naive; i++) {
     const float li = a.naive_lse[(size_t)i * a.rows + row];
     if (li == -INFINITY) continue;
     const float w = __expf(li - m2);
     z2 += w;
-    const float* src = a.naive_o + ((size_t)i * a.rows + row) * D_V + 4 * g;
+    const float* src = a.naive_o + ((size_t)i * a.rows + row) * D_V + 32 * wave + 4 * g;
 #pragma unroll
-    for (int mb = 0; mb < 4; mb++)
-#pragma unroll
-      for (int v4 = 0; v4 < 4; v4++) {
-        const float4 x = *(const float4*)(src + 32 * mb + 8 * v4);
-        acc[mb][4 * v4] += w * x.x; acc[mb][4 * v4 + 1] += w * x.y;
-        acc[mb][4 * v4 + 2] += w * x.z; acc[mb][4 * v4 + 3] += w * x.w;
-      }
+    for (int v4 = 0; v4 < 4; v4++) {
+      const float4 x = *(const float4*)(src + 8 * v4);
+      oa[4 * v4] += w * x.x; oa[4 * v4 + 1] += w * x.y;
+      oa[4 * v4 + 2] += w * x.z; oa[4 * v4 + 3] += w * x.w;
+    }
   }
   const float inv2 = 1.f / z2;
 #pragma unroll
-  for (int mb = 0; mb < 4; mb++)
+  for (int v4 = 0; v4 < 4; v4++) {
+    bf16x4 w;
 #pragma unroll
-    for (int v4 = 0; v4 < 4; v4++) {
-      bf16x4 w;
-#pragma unroll
-      for (int e = 0; e < 4; e++) w[e] = (__bf16)(acc[mb][4 * v4 + e] * inv2);
-      *(bf16x4*)(dst + 32 * mb + 8 * v4 + 4 * g) = w;
-    }
-  if (a.lse_out && g == 0) a.lse_out[row] = m2 + __logf(z2);
+    for (int e = 0; e < 4; e++) w[e] = (__bf16)(oa[4 * v4 + e] * inv2);
+    *(bf16x4*)(dst + 8 * v4) = w;
+  }
+  if (a.lse_out && wave == 0 && g == 0) a.lse_out[row] = m2 + __logf(z2);
 }
 
 int mfma_finalize(const Plan& p, const DecodeArgs& d) {
@@ -227,7 +233,7 @@ int mfma_finalize(const Plan& p, const DecodeArgs& d) {
   a.out = (__bf16*)d.out;
   a.lse_out = d.lse_out;
   a.M = p.B * p.Sq; a.H = p.H; a.n_naive = p.n_naive; a.n_lat = p.n_lat; a.rows = p.rows;
-  dim3 grid(p.H, (a.M + 127) / 128);
+  dim3 grid(p.H, (a.M + 31) / 32);
   hipLaunchKernelGGL(finalize_kernel, grid, dim3(256), 0, d.stream, a);
   return TMLA_OK;
 }
