@@ -34,6 +34,8 @@ def parse_args():
     ap.add_argument("--modes", default="mixed,absorb_only,naive_only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stages", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference for HBM counters)")
     ap.add_argument("--cpu-sample-requests", type=int, default=0,
                     help="requests (all heads each) in the oracle sample; 0 = auto")
     return ap.parse_args()
@@ -136,6 +138,16 @@ def main():
                              suffix_lens=d.suffix_lens, max_suffix_len=wl.max_suffix_len,
                              suffix_k_pool=sk, suffix_v_pool=sv, w_uk=d.w_uk, w_uv=d.w_uv,
                              out=out, lse_out=lse, workspace=ws[mode])
+
+    if args.calibrate_copy:
+        # a plain copy of known size: rocprofv3's FETCH_SIZE / WRITE_SIZE for this kernel give the
+        # scale factor of the HBM traffic counters
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- the timed region: exactly K steps of the whole hot path, inputs resident in HBM
     ms = {}

@@ -40,7 +40,6 @@ struct AbsorbArgs {
   int Sq, H, R, Ls, ap_chunks, ap_chunk, as_chunk, max_blocks, block_size;
   int64_t rows;
   float c;                   // sm_scale * log2(e)
-  int dbg;
 };
 
 // LDS tile of 32 tokens (37888 B):
@@ -119,7 +118,7 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
   const int lane_off0 = lane << 4, lane_off1 = (lane ^ 1) << 4;
   const int rope_row = 8 * wave + (lane >> 3);
   const int rope_ch = ((lane & 7) ^ ((lane >> 3) & 7)) << 4;
-  auto issue_tile = [&](int tile, auto prefix_tag) {
+  auto issue_tile = [&](int tile, auto prefix_tag) __attribute__((always_inline)) {
     constexpr bool PREFIX = decltype(prefix_tag)::value;
     const int tok0 = t0 + tile * 32;
     const int last = t1 - 1 - tok0;      // last valid row of this tile (>= 0)
@@ -149,7 +148,7 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
       dma16(src, dst + AB_MAIN_BYTES + wave * 1024);
     }
   };
-  auto issue = [&](int tile) {
+  auto issue = [&](int tile) __attribute__((always_inline)) {
     if (is_prefix) issue_tile(tile, std::true_type{});
     else issue_tile(tile, std::false_type{});
   };
@@ -189,8 +188,7 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
     else if (ahead == 1) vm_wait<AB_DMA_PER_WAVE>();
     else vm_wait<0>();
     raw_barrier();   // everyone's part of `tile` has landed; everyone is done with tile - 1
-    if (tile + AB_NSLOT - 1 < ntile && !(a.dbg & 2)) issue(tile + AB_NSLOT - 1);
-    if (a.dbg & 1) continue;
+    if (tile + AB_NSLOT - 1 < ntile) issue(tile + AB_NSLOT - 1);
 
     const uint32_t tbase = smem_base + (tile % AB_NSLOT) * AB_TILE_BYTES;
     const uint32_t sa = tbase + s_off;
@@ -288,6 +286,7 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
 
 int mfma_absorb_attention(const Plan& p, const DecodeArgs& d) {
   if (p.n_lat <= 0 || p.rows == 0) return TMLA_OK;
+  if (p.Sq * p.H <= 16) return mfma_absorb16_attention(p, d);
   AbsorbArgs a;
   a.qabs = (const __bf16*)(d.ws + p.off_qabs);
   a.pc = (const __bf16*)d.prefix_ckv;
@@ -302,7 +301,6 @@ int mfma_absorb_attention(const Plan& p, const DecodeArgs& d) {
   a.max_blocks = d.max_blocks; a.block_size = d.block_size;
   a.rows = p.rows;
   a.c = d.sm_scale * LOG2E;
-  a.dbg = getenv("TMLA_ABSORB_DBG") ? atoi(getenv("TMLA_ABSORB_DBG")) : 0;
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)absorb_attn_kernel<4>,

@@ -67,21 +67,24 @@ int make_plan(const tmla_dims* dims, int mode, int B, int Sq, int Ls, int max_su
     p->ns_chunks = ceil_div(max_suffix, p->ns_chunk);
   }
   if (mode != TMLA_MODE_NAIVE_ONLY) {
-    // absorb pass: one workgroup owns a request and up to 128 of its S_q*H query rows
-    const int wgs = std::max(1, B * ceil_div(Sq * H, 128));
+    // absorb pass: one workgroup owns a request, one token chunk and up to 64 of its S_q*H query
+    // rows (with at most 16 rows: four consecutive chunks, one per wavefront).  Chunks are kept
+    // as long as the grid still covers the chip about twice: every extra chunk costs a
+    // 512-wide fp32 partial per row and a workgroup start-up.
+    const int R = Sq * H;
+    const int per_wg = R <= 16 ? 4 : 1;
+    const int wgs = std::max(1, B * ceil_div(R, 64));
+    const int want = std::max(1, ceil_div(2 * NUM_CU, wgs)) * per_wg;   // chunks per request
     if (mode == TMLA_MODE_ABSORB_ONLY && Ls > 0) {
       int chunk = env_int("TMLA_ABSORB_PREFIX_CHUNK", 0);
-      if (chunk <= 0) chunk = std::max(512, round_up(ceil_div(Ls, std::max(1, ceil_div(2 * target, wgs))), 256));
+      if (chunk <= 0) chunk = std::max(256, ceil_div(Ls, want));
       chunk = std::max(chunk, ceil_div(Ls, MAX_CHUNKS));
       p->ap_chunk = round_up(std::min(chunk, round_up(Ls, TOK_BLK)), TOK_BLK);
       p->ap_chunks = ceil_div(Ls, p->ap_chunk);
     }
     if (max_suffix > 0) {
       int chunk = env_int("TMLA_SUFFIX_CHUNK", 0);
-      if (chunk <= 0) {
-        const int want = std::max(1, ceil_div(2 * target, wgs));  // chunks per request wanted
-        chunk = std::max(256, ceil_div(max_suffix, want));
-      }
+      if (chunk <= 0) chunk = std::max(256, ceil_div(max_suffix, want));
       chunk = std::max(chunk, ceil_div(max_suffix, MAX_CHUNKS));
       p->as_chunk = round_up(std::min(chunk, round_up(max_suffix, block_size)), block_size);
       p->as_chunks = ceil_div(max_suffix, p->as_chunk);

@@ -114,6 +114,7 @@ int mfma_expand(int H, int64_t ntok, const void* c, int64_t c_stride, const void
 int mfma_prefix_attention(const Plan& p, const DecodeArgs& a);
 int mfma_query_absorb(const Plan& p, const DecodeArgs& a);
 int mfma_absorb_attention(const Plan& p, const DecodeArgs& a);
+int mfma_absorb16_attention(const Plan& p, const DecodeArgs& a);   // S_q * H <= 16
 int mfma_finalize(const Plan& p, const DecodeArgs& a);
 constexpr int MAX_CHUNKS = 32;  // per-request chunk bound for each of the latent prefix / suffix
 void launch_combine_lse(int num_partials, int64_t rows, int width, const float* po,

@@ -92,6 +92,11 @@ __device__ inline void dma16(const void* src, void* dst) {
 // Scalar (SMEM) load of one int from a wave-uniform address.  A vector load here would have to be
 // waited for with vmcnt(0), draining the tile prefetch; the scalar cache is only read.
 __device__ inline int scalar_load_i32(const int32_t* p) {
+  // the address is wave-uniform by contract; make that explicit so it lives in scalar registers
+  const uint64_t u = (uint64_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+  p = (const int32_t*)(((uint64_t)hi << 32) | lo);
   int v;
   asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(p) : "memory");
   return v;

@@ -16,9 +16,6 @@
 //     softmaxes are merged through LDS at the end.  Used for small batches, the HBM-bound regime.
 // Split-K over the prefix comes on top (grid.z); each workgroup writes a normalised partial
 // output and its natural-log LSE for the combine step.
-#include <cstdio>
-#include <cstdlib>
-
 #include "tmla_common.hpp"
 #include "tmla_lds_asm.hpp"
 #include "tmla_mfma.hpp"
@@ -34,7 +31,6 @@ struct PrefixArgs {
   int M, H, Ls, ntb, blocks_per_split;
   int64_t rows;
   float c;            // sm_scale * log2(e)
-  int dbg;
 };
 
 __device__ inline void load_q_frags(const PrefixArgs& a, int h, int q0, int n, int g,
@@ -181,8 +177,8 @@ __global__ void __launch_bounds__(QS_WAVES * 64, 1) prefix_attn_query_split_kern
     const int newest = min(nblk - 1, i + QS_AHEAD - 1);   // newest block issued so far
     if (k_mover) qs_wait_pending<3>(newest - i);
     else qs_wait_pending<2>(newest - i);
-    if (!(a.dbg & 16)) raw_barrier();
-    if (i + QS_AHEAD < nblk && !(a.dbg & 8)) issue(i + QS_AHEAD);
+    raw_barrier();
+    if (i + QS_AHEAD < nblk) issue(i + QS_AHEAD);
   };
   auto blk_addr = [&](int i) { return smem_addr + (i % QS_NSLOT) * QS_BLOCK_BYTES; };
   auto rescale_o = [&](float alpha, bool resc) {
@@ -205,9 +201,7 @@ __global__ void __launch_bounds__(QS_WAVES * 64, 1) prefix_attn_query_split_kern
   const int tail_limit = a.Ls - (tb0 + nblk - 1) * TOK_BLK;   // valid tokens of a partial tail
   bf16x8 p_a[2], p_b[2];
   bool resc;
-  const bool group_a = a.dbg == 1 ? (wave & 1) == 0 : a.dbg == 2 ? ((wave >> 1) & 1) == 0
-                       : a.dbg == 3 ? true : wave < 4;
-  if (group_a) {
+  if (wave < 4) {
     auto phase = [&](int i, bf16x8 (&p_out)[2], const bf16x8 (&p_in)[2]) {
       sync_and_refill(i);
       f32x16 s = qs_scores(blk_addr(i), qf);
@@ -475,7 +469,6 @@ int mfma_prefix_attention(const Plan& p, const DecodeArgs& d) {
   a.blocks_per_split = p.p_chunk / TOK_BLK;
   a.rows = p.rows;
   a.c = d.sm_scale * LOG2E;
-  a.dbg = getenv("TMLA_PREFIX_DBG") ? atoi(getenv("TMLA_PREFIX_DBG")) : 0;
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)prefix_attn_query_split_kernel,
