@@ -229,6 +229,18 @@ def main():
             roofline["mfma_frac"] = w["flops"] / t / MFMA_BF16_PEAK
             roofline["hbm_frac"] = w["bytes"] / t / HBM_PEAK
     result["roofline"] = roofline
+    # every attention kernel against both ceilings (the dominant one is in "roofline")
+    per_kernel = {}
+    for name, w in (("prefix_attention", C.prefix_kernel_work(shape, 1) if L_s else None),
+                    ("absorb_attention", C.suffix_kernel_work(shape, 0))):
+        if w is None or name not in stage_ms:
+            continue
+        t = stage_ms[name] * 1e-3
+        per_kernel[name] = {"ms": stage_ms[name], "GB/s": w["bytes"] / t / 1e9,
+                            "hbm_frac": w["bytes"] / t / HBM_PEAK,
+                            "TFLOP/s": w["flops"] / t / 1e12,
+                            "mfma_frac": w["flops"] / t / MFMA_BF16_PEAK}
+    result["kernel_rooflines"] = per_kernel
 
     # ---- CPU baseline: the fp64 oracle as it stands, on a bounded sample of the same workload,
     # which also serves as a parity check of the timed output
@@ -243,9 +255,12 @@ def main():
         a = wl.as_float64()
         n_req = args.cpu_sample_requests
         if n_req <= 0:
-            # the cost is dominated by up-projecting every visible token once per head; keep the
-            # sample to a few requests so this leg stays within tens of seconds
-            n_req = 4 if L_s * H <= (1 << 20) else 2
+            # the cost is dominated by up-projecting every visible token once per head; the
+            # small configurations run in full, the large ones on a few requests, which keeps
+            # this leg to roughly 10-30 s of CPU work
+            per_req = (sum_ln / max(1, B)) * H * 131072.0
+            budget = 1.5e12 - L_s * H * 131072.0          # MACs, at ~1e11 fp64 MAC/s
+            n_req = int(max(2, min(B, budget / max(per_req, 1.0))))
         reqs = sorted({0, B - 1} | set(range(0, B, max(1, B // n_req))))[:max(n_req, 1)]
         reqs = [b for b in reqs if b < B]
         pairs = [(b, h) for b in reqs for h in range(H)]

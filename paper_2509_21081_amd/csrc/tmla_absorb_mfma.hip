@@ -12,11 +12,11 @@
 // product straight from the accumulator registers.
 //
 // Wavefront roles (template NQB = query blocks of 32 rows per workgroup, NQB * NLP = 4):
-//   NQB = 4: four wavefronts own 4 x 32 query rows and all 512 latent columns each  (H >= 128)
+//   NQB = 4: four wavefronts own 4 x 32 query rows and all 512 latent columns each (not built:
+//            it needs more registers than a wavefront has)
 //   NQB = 2: 2 x 32 query rows, two wavefronts per block own 256 latent columns each
 //   NQB = 1: 32 query rows (H = 16 with S_q <= 2), four wavefronts own 128 latent columns each;
 //            the scores are recomputed per wavefront, which the HBM-bound small-H case affords.
-#include <cstdlib>
 #include <type_traits>
 #include <utility>
 
@@ -303,9 +303,7 @@ int mfma_absorb_attention(const Plan& p, const DecodeArgs& d) {
   a.c = d.sm_scale * LOG2E;
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)absorb_attn_kernel<4>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, AB_LDS_BYTES) != hipSuccess ||
-        hipFuncSetAttribute((const void*)absorb_attn_kernel<2>,
+    if (hipFuncSetAttribute((const void*)absorb_attn_kernel<2>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, AB_LDS_BYTES) != hipSuccess ||
         hipFuncSetAttribute((const void*)absorb_attn_kernel<1>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, AB_LDS_BYTES) != hipSuccess)
@@ -313,11 +311,10 @@ int mfma_absorb_attention(const Plan& p, const DecodeArgs& d) {
     attr_set = true;
   }
   const int R = a.R;
-  static const int force_nqb4 = getenv("TMLA_ABSORB_NQB4") ? atoi(getenv("TMLA_ABSORB_NQB4")) : 0;
-  if (R > 64 && force_nqb4) {
-    dim3 grid(p.n_lat, (R + 127) / 128, p.B);
-    hipLaunchKernelGGL(absorb_attn_kernel<4>, grid, dim3(256), AB_LDS_BYTES, d.stream, a);
-  } else if (R > 32) {
+  // 128 rows per workgroup (NQB = 4) would read each tile once instead of twice, but its
+  // accumulators (256 registers) plus query fragments (144) do not fit without spills, and a
+  // spill reload inside the loop drains the tile prefetch; 64 rows per workgroup it is.
+  if (R > 32) {
     dim3 grid(p.n_lat, (R + 63) / 64, p.B);
     hipLaunchKernelGGL(absorb_attn_kernel<2>, grid, dim3(256), AB_LDS_BYTES, d.stream, a);
   } else {

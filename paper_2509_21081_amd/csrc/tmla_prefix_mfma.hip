@@ -16,6 +16,8 @@
 //     softmaxes are merged through LDS at the end.  Used for small batches, the HBM-bound regime.
 // Split-K over the prefix comes on top (grid.z); each workgroup writes a normalised partial
 // output and its natural-log LSE for the combine step.
+#include <type_traits>
+
 #include "tmla_common.hpp"
 #include "tmla_lds_asm.hpp"
 #include "tmla_mfma.hpp"
@@ -48,22 +50,24 @@ __device__ inline void load_q_frags(const PrefixArgs& a, int h, int q0, int n, i
 }
 
 // ------------------------------------------------------------------ query-split workgroup
-// Eight wavefronts (two per SIMD, so one wavefront's softmax overlaps the other's MFMAs), each
-// owning 32 queries of the head; K/V blocks stream global -> LDS through a ring of QS_NSLOT
-// blocks shared by all of them.  Per wavefront the work on block i is
+// 256 queries of a head per workgroup; K/V blocks stream global -> LDS through a ring of QS_NSLOT
+// blocks shared by all wavefronts.  Per wavefront the work on block i is
 //     scores (MFMA)  ->  softmax (VALU) side by side with P V of block i-1 (MFMA).
+// Template NB = 32-query column blocks per wavefront:
+//   NB = 1: eight wavefronts (two per SIMD) x 32 queries, every LDS fragment feeds one MFMA;
+//   NB = 2: four wavefronts x 64 queries, every LDS fragment feeds two MFMAs (half the LDS
+//           traffic per flop, but the whole register file of a SIMD for one wavefront).
 constexpr int QS_BLOCK_BYTES = (K_BLK_ELEMS + V_BLK_ELEMS) * 2;  // 20480 = 20 x 1 KiB
 constexpr int QS_NSLOT = 7;
 constexpr int QS_LDS_BYTES = QS_NSLOT * QS_BLOCK_BYTES;           // 143360
-constexpr int QS_AHEAD = QS_NSLOT - 2;   // blocks in flight beyond the two being worked on
-constexpr int QS_WAVES = 8;
-constexpr int QS_QUERIES = QS_WAVES * 32;
+constexpr int QS_AHEAD = 4;   // blocks issued ahead of the pair being synchronised
+constexpr int QS_QUERIES = 256;
 
-// scores of one 32-token block for this wavefront's 32 queries: K_block(32 x 192) Q^T, with the
+// scores of one 32-token block for this wavefront's queries: K_block(32 x 192) Q^T, with the
 // K fragments read from the LDS block whose lane address is `ka`
-__device__ inline f32x16 qs_scores(uint32_t ka, const bf16x8 (&qf)[12]) {
+template <int NB>
+__device__ inline void qs_scores(uint32_t ka, const bf16x8 (&qf)[NB][12], f32x16 (&sacc)[NB]) {
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  f32x16 sacc;
   bf16x8 f[2][4];
   static_for<4>([&](auto j) { f[0][j] = lds_read_b128<1024 * decltype(j)::value>(ka); });
   static_for<3>([&](auto grp) {
@@ -79,25 +83,32 @@ __device__ inline f32x16 qs_scores(uint32_t ka, const bf16x8 (&qf)[12]) {
     }
     static_for<4>([&](auto j) {
       constexpr int ks = 4 * G + decltype(j)::value;
-      if constexpr (ks == 0) sacc = mfma32(f[cur][j], qf[ks], zero);
-      else sacc = mfma32(f[cur][j], qf[ks], sacc);
+#pragma unroll
+      for (int nb = 0; nb < NB; nb++) {
+        if constexpr (ks == 0) sacc[nb] = mfma32(f[cur][j], qf[nb][ks], zero);
+        else sacc[nb] = mfma32(f[cur][j], qf[nb][ks], sacc[nb]);
+      }
     });
   });
-  return sacc;
 }
 
 // o += V_block^T P^T, V fragments from the LDS block whose lane address is `ka`
-__device__ inline void qs_pv(uint32_t ka, const bf16x8 (&p)[2], f32x16 (&o)[4]) {
+template <int NB>
+__device__ inline void qs_pv(uint32_t ka, const bf16x8 (&p)[NB][2], f32x16 (&o)[4][NB]) {
   bf16x8 vf[8];
   static_for<8>([&](auto j) {
     vf[j] = lds_read_b128<K_BLK_ELEMS * 2 + 1024 * decltype(j)::value>(ka);
   });
   lgkm_wait<4>(vf[0], vf[1], vf[2], vf[3]);
 #pragma unroll
-  for (int db = 0; db < 4; db++) o[db] = mfma32(vf[db], p[0], o[db]);
+  for (int db = 0; db < 4; db++)
+#pragma unroll
+    for (int nb = 0; nb < NB; nb++) o[db][nb] = mfma32(vf[db], p[nb][0], o[db][nb]);
   lgkm_wait<0>(vf[4], vf[5], vf[6], vf[7]);
 #pragma unroll
-  for (int db = 0; db < 4; db++) o[db] = mfma32(vf[4 + db], p[1], o[db]);
+  for (int db = 0; db < 4; db++)
+#pragma unroll
+    for (int nb = 0; nb < NB; nb++) o[db][nb] = mfma32(vf[4 + db], p[nb][1], o[db][nb]);
 }
 
 template <int PER_BLOCK>
@@ -109,12 +120,14 @@ __device__ inline void qs_wait_pending(int pending) {
   else vm_wait<0>();
 }
 
-__global__ void __launch_bounds__(QS_WAVES * 64, 1) prefix_attn_query_split_kernel(PrefixArgs a) {
+template <int NB>
+__global__ void __launch_bounds__(512 / NB, 1) prefix_attn_query_split_kernel(PrefixArgs a) {
+  constexpr int NWAVE = 8 / NB;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int h = blockIdx.x, mb = blockIdx.y, sp = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int qi = mb * QS_QUERIES + wave * 32 + n;   // this lane's query
+  const int q0 = mb * QS_QUERIES + wave * (32 * NB);   // first query of this wavefront
 
   const int tb0 = sp * a.blocks_per_split;
   const int tb1 = min(a.ntb, tb0 + a.blocks_per_split);
@@ -124,23 +137,26 @@ __global__ void __launch_bounds__(QS_WAVES * 64, 1) prefix_attn_query_split_kern
   const int nfull = has_tail ? nblk - 1 : nblk;
   const uint32_t smem_addr = lds_addr(smem) + lane * 16;
 
-  // transfers per block: wavefronts 0-3 move K fragments w, w+4, w+8; wavefronts 4-7 move V
-  // fragments w-4 and w
-  const bool k_mover = wave < 4;
-  const char* src = k_mover
-      ? (const char*)(a.pk + ((size_t)h * a.ntb + tb0) * K_BLK_ELEMS) + wave * 1024 + lane * 16
-      : (const char*)(a.pv + ((size_t)h * a.ntb + tb0) * V_BLK_ELEMS) + (wave - 4) * 1024 + lane * 16;
-  auto issue = [&](int i) {
+  // 20 transfers of 1 KiB per block (fragments 0-11 = K, 12-19 = V), spread over the wavefronts:
+  //   8 wavefronts: 0-3 move K fragments w, w+4, w+8; 4-7 move V fragments w-4, w
+  //   4 wavefronts: each moves K fragments w, w+4, w+8 and V fragments w, w+4
+  const bool k_mover = NWAVE == 4 || wave < 4;
+  const bool v_mover = NWAVE == 4 || wave >= 4;
+  const int wq = wave & 3;
+  const char* ksrc = (const char*)(a.pk + ((size_t)h * a.ntb + tb0) * K_BLK_ELEMS) + wq * 1024 + lane * 16;
+  const char* vsrc = (const char*)(a.pv + ((size_t)h * a.ntb + tb0) * V_BLK_ELEMS) + wq * 1024 + lane * 16;
+  auto issue = [&](int i) __attribute__((always_inline)) {
     char* slot = smem + (i % QS_NSLOT) * QS_BLOCK_BYTES;
     if (k_mover) {
-      const char* s0 = src + (size_t)i * (K_BLK_ELEMS * 2);
-      char* dst = slot + wave * 1024;
+      const char* s0 = ksrc + (size_t)i * (K_BLK_ELEMS * 2);
+      char* dst = slot + wq * 1024;
       dma16(s0, dst);
       dma16(s0 + 4096, dst + 4096);
       dma16(s0 + 8192, dst + 8192);
-    } else {
-      const char* s0 = src + (size_t)i * (V_BLK_ELEMS * 2);
-      char* dst = slot + K_BLK_ELEMS * 2 + (wave - 4) * 1024;
+    }
+    if (v_mover) {
+      const char* s0 = vsrc + (size_t)i * (V_BLK_ELEMS * 2);
+      char* dst = slot + K_BLK_ELEMS * 2 + wq * 1024;
       dma16(s0, dst);
       dma16(s0 + 4096, dst + 4096);
     }
@@ -149,119 +165,154 @@ __global__ void __launch_bounds__(QS_WAVES * 64, 1) prefix_attn_query_split_kern
   for (int i = 0; i < QS_AHEAD; i++)
     if (i < nblk) issue(i);
 
-  bf16x8 qf[12];
-  {
+  bf16x8 qf[NB][12];
+#pragma unroll
+  for (int nb = 0; nb < NB; nb++) {
+    const int qi = q0 + nb * 32 + n;
     const __bf16* p = a.q + ((size_t)qi * a.H + h) * D_QK + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < 12; ks++) {
       bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-      qf[ks] = (qi < a.M) ? *(const bf16x8*)(p + 16 * ks) : z;
+      qf[nb][ks] = (qi < a.M) ? *(const bf16x8*)(p + 16 * ks) : z;
     }
   }
 #pragma unroll
-  for (int ks = 0; ks < 12; ks += 4)
-    asm volatile("s_waitcnt vmcnt(0)"
-                 : "+v"(qf[ks]), "+v"(qf[ks + 1]), "+v"(qf[ks + 2]), "+v"(qf[ks + 3])::"memory");
+  for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+    for (int ks = 0; ks < 12; ks += 4)
+      if constexpr (NB == 2)   // one wavefront per SIMD: park the fragments in accumulator registers
+        asm volatile("s_waitcnt vmcnt(0)"
+                     : "+a"(qf[nb][ks]), "+a"(qf[nb][ks + 1]), "+a"(qf[nb][ks + 2]),
+                       "+a"(qf[nb][ks + 3])::"memory");
+      else
+        asm volatile("s_waitcnt vmcnt(0)"
+                     : "+v"(qf[nb][ks]), "+v"(qf[nb][ks + 1]), "+v"(qf[nb][ks + 2]),
+                       "+v"(qf[nb][ks + 3])::"memory");
 
-  f32x16 o[4];
+  f32x16 o[4][NB];
 #pragma unroll
   for (int db = 0; db < 4; db++)
 #pragma unroll
-    for (int v = 0; v < 16; v++) o[db][v] = 0.f;
-  float m = -INFINITY, l = 0.f;
+    for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) o[db][nb][v] = 0.f;
+  float m[NB], l[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; nb++) { m[nb] = -INFINITY; l[nb] = 0.f; }
 
-  // Block i may be read once (a) this wavefront's transfers of it are done and (b) the barrier
-  // has been passed by everyone after their own wait.  Called exactly once per block, in order;
-  // after it, everybody has also finished reading block i-2, whose slot is refilled.
-  auto sync_and_refill = [&](int i) {
+  // Blocks are synchronised in pairs (i even): blocks i and i+1 may be read once (a) this
+  // wavefront's transfers of them are done and (b) the barrier has been passed by everyone after
+  // their own wait.  Called once per pair, in order; after it everybody has also finished the
+  // previous pair's period, which was the last reader of blocks i-3 and i-2 (7 slots: three
+  // blocks in use -- V of i-1, K/V of i and i+1 -- and four in flight), so i+4 and i+5 are issued.
+  auto sync_pair = [&](int i) __attribute__((always_inline)) {
     const int newest = min(nblk - 1, i + QS_AHEAD - 1);   // newest block issued so far
-    if (k_mover) qs_wait_pending<3>(newest - i);
-    else qs_wait_pending<2>(newest - i);
+    const int pending = newest - min(nblk - 1, i + 1);    // blocks issued after the pair
+    if (NWAVE == 4) qs_wait_pending<5>(pending);
+    else if (k_mover) qs_wait_pending<3>(pending);
+    else qs_wait_pending<2>(pending);
     raw_barrier();
     if (i + QS_AHEAD < nblk) issue(i + QS_AHEAD);
+    if (i + QS_AHEAD + 1 < nblk) issue(i + QS_AHEAD + 1);
   };
   auto blk_addr = [&](int i) { return smem_addr + (i % QS_NSLOT) * QS_BLOCK_BYTES; };
-  auto rescale_o = [&](float alpha, bool resc) {
-    if (resc) {
+  // softmax of the scores `s` (all column blocks) into `p`, then rescale of the outputs
+  float alpha[NB];
+  bool resc[NB];
+  auto softmax_all = [&](f32x16 (&s)[NB], bf16x8 (&p)[NB][2], auto mask_tag, int limit)
+                         __attribute__((always_inline)) {
 #pragma unroll
-      for (int db = 0; db < 4; db++)
+    for (int nb = 0; nb < NB; nb++)
+      alpha[nb] = softmax_block<decltype(mask_tag)::value>(s[nb], m[nb], l[nb], a.c, limit, g,
+                                                           p[nb][0], p[nb][1], resc[nb]);
+  };
+  auto rescale_o = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int v = 0; v < 16; v++) o[db][v] *= alpha;
-    }
+    for (int nb = 0; nb < NB; nb++)
+      if (resc[nb]) {
+#pragma unroll
+        for (int db = 0; db < 4; db++)
+#pragma unroll
+          for (int v = 0; v < 16; v++) o[db][nb][v] *= alpha[nb];
+      }
   };
 
-  // One pipeline phase for full block i: its scores (matrix core), then its softmax (vector
-  // ALU) side by side with P V of block i-1 (matrix core), which uses the previous phase's P.
-  // The two wavefronts that share a SIMD (w and w+4) run the same work in a different order so
-  // that one is on the matrix core while the other is on the vector ALU:
-  //   wavefronts 0-3, period i:  scores(i)     -> softmax(i)   -> P V(i-1)
-  //   wavefronts 4-7, period i:  softmax(i-1)  -> scores(i)    -> P V(i-1)
+  // With two wavefronts per SIMD (NB = 1), the pair (w, w+4) runs the same work in a different
+  // order so that one is on the matrix core while the other is on the vector ALU:
+  //   first group, period i:   scores(i)     -> softmax(i)   -> P V(i-1)
+  //   second group, period i:  softmax(i-1)  -> scores(i)    -> P V(i-1)
   // Both read K of block i and V of block i-1 in period i, so the ring bookkeeping is the same,
-  // and both call sync_and_refill exactly once per block.
+  // and both call sync_pair exactly once per pair of blocks.
   const int tail_limit = a.Ls - (tb0 + nblk - 1) * TOK_BLK;   // valid tokens of a partial tail
-  bf16x8 p_a[2], p_b[2];
-  bool resc;
-  if (wave < 4) {
-    auto phase = [&](int i, bf16x8 (&p_out)[2], const bf16x8 (&p_in)[2]) {
-      sync_and_refill(i);
-      f32x16 s = qs_scores(blk_addr(i), qf);
-      const float alpha = softmax_block<false>(s, m, l, a.c, 32, g, p_out[0], p_out[1], resc);
-      if (i > 0) qs_pv(blk_addr(i - 1), p_in, o);
-      rescale_o(alpha, resc);
+  bf16x8 p_a[NB][2], p_b[NB][2];
+  if (NWAVE == 4 || wave < 4) {
+    auto phase = [&](int i, bf16x8 (&p_out)[NB][2], const bf16x8 (&p_in)[NB][2])
+                     __attribute__((always_inline)) {
+      if ((i & 1) == 0) sync_pair(i);
+      f32x16 s[NB];
+      qs_scores<NB>(blk_addr(i), qf, s);
+      softmax_all(s, p_out, std::false_type{}, 32);
+      if (i > 0) qs_pv<NB>(blk_addr(i - 1), p_in, o);
+      rescale_o();
     };
     for (int i = 0; i < nfull; i += 2) {
       phase(i, p_a, p_b);
       if (i + 1 < nfull) phase(i + 1, p_b, p_a);
     }
-    if (has_tail) sync_and_refill(nblk - 1);
+    if (has_tail && (nfull & 1) == 0) sync_pair(nfull);
     if (nfull > 0) {
-      if (nfull & 1) qs_pv(blk_addr(nfull - 1), p_a, o);
-      else qs_pv(blk_addr(nfull - 1), p_b, o);
+      if (nfull & 1) qs_pv<NB>(blk_addr(nfull - 1), p_a, o);
+      else qs_pv<NB>(blk_addr(nfull - 1), p_b, o);
     }
   } else {
-    f32x16 s_hold;
+    f32x16 s_hold[NB];
     if (nfull > 0) {
-      sync_and_refill(0);
-      s_hold = qs_scores(blk_addr(0), qf);
+      sync_pair(0);
+      qs_scores<NB>(blk_addr(0), qf, s_hold);
     }
     for (int i = 1; i < nfull; i++) {
-      sync_and_refill(i);
-      const float alpha = softmax_block<false>(s_hold, m, l, a.c, 32, g, p_a[0], p_a[1], resc);
-      rescale_o(alpha, resc);
-      s_hold = qs_scores(blk_addr(i), qf);
-      qs_pv(blk_addr(i - 1), p_a, o);
+      if ((i & 1) == 0) sync_pair(i);
+      softmax_all(s_hold, p_a, std::false_type{}, 32);
+      rescale_o();
+      qs_scores<NB>(blk_addr(i), qf, s_hold);
+      qs_pv<NB>(blk_addr(i - 1), p_a, o);
     }
-    if (has_tail) sync_and_refill(nblk - 1);
+    if (has_tail && (nfull & 1) == 0) sync_pair(nfull);
     if (nfull > 0) {
-      const float alpha = softmax_block<false>(s_hold, m, l, a.c, 32, g, p_a[0], p_a[1], resc);
-      rescale_o(alpha, resc);
-      qs_pv(blk_addr(nfull - 1), p_a, o);
+      softmax_all(s_hold, p_a, std::false_type{}, 32);
+      rescale_o();
+      qs_pv<NB>(blk_addr(nfull - 1), p_a, o);
     }
   }
   if (has_tail) {   // partial last block of the prefix: plain masked pass
     const int i = nblk - 1;
-    f32x16 s = qs_scores(blk_addr(i), qf);
-    const float alpha = softmax_block<true>(s, m, l, a.c, tail_limit, g, p_a[0], p_a[1], resc);
-    rescale_o(alpha, resc);
-    qs_pv(blk_addr(i), p_a, o);
+    f32x16 s[NB];
+    qs_scores<NB>(blk_addr(i), qf, s);
+    softmax_all(s, p_a, std::true_type{}, tail_limit);
+    rescale_o();
+    qs_pv<NB>(blk_addr(i), p_a, o);
   }
 
-  const float lt = sum_halves(l);
-  if (qi >= a.M) return;
-  const size_t row = (size_t)sp * a.rows + (size_t)qi * a.H + h;
-  if (lt > 0.f) {
-    const float inv = 1.f / lt;
 #pragma unroll
-    for (int db = 0; db < 4; db++)
+  for (int nb = 0; nb < NB; nb++) {
+    const int qi = q0 + nb * 32 + n;
+    const float lt = sum_halves(l[nb]);
+    if (qi >= a.M) continue;
+    const size_t row = (size_t)sp * a.rows + (size_t)qi * a.H + h;
+    if (lt > 0.f) {
+      const float inv = 1.f / lt;
 #pragma unroll
-      for (int v4 = 0; v4 < 4; v4++) {
-        float4 w = make_float4(o[db][4 * v4] * inv, o[db][4 * v4 + 1] * inv,
-                               o[db][4 * v4 + 2] * inv, o[db][4 * v4 + 3] * inv);
-        *(float4*)(a.o + row * D_V + 32 * db + 8 * v4 + 4 * g) = w;
-      }
-    if (g == 0) a.lse[row] = (m + fast_log2(lt)) * LN2;
-  } else if (g == 0) {
-    a.lse[row] = -INFINITY;
+      for (int db = 0; db < 4; db++)
+#pragma unroll
+        for (int v4 = 0; v4 < 4; v4++) {
+          float4 w = make_float4(o[db][nb][4 * v4] * inv, o[db][nb][4 * v4 + 1] * inv,
+                                 o[db][nb][4 * v4 + 2] * inv, o[db][nb][4 * v4 + 3] * inv);
+          *(float4*)(a.o + row * D_V + 32 * db + 8 * v4 + 4 * g) = w;
+        }
+      if (g == 0) a.lse[row] = (m[nb] + fast_log2(lt)) * LN2;
+    } else if (g == 0) {
+      a.lse[row] = -INFINITY;
+    }
   }
 }
 
@@ -471,7 +522,7 @@ int mfma_prefix_attention(const Plan& p, const DecodeArgs& d) {
   a.c = d.sm_scale * LOG2E;
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)prefix_attn_query_split_kernel,
+    if (hipFuncSetAttribute((const void*)prefix_attn_query_split_kernel<1>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, QS_LDS_BYTES) != hipSuccess ||
         hipFuncSetAttribute((const void*)prefix_attn_token_split_kernel,
                             hipFuncAttributeMaxDynamicSharedMemorySize, TS_LDS_BYTES) != hipSuccess)
@@ -480,8 +531,11 @@ int mfma_prefix_attention(const Plan& p, const DecodeArgs& d) {
   }
   if (a.M > 128) {
     dim3 grid(p.H, (a.M + QS_QUERIES - 1) / QS_QUERIES, p.np_split);
-    hipLaunchKernelGGL(prefix_attn_query_split_kernel, grid, dim3(QS_WAVES * 64), QS_LDS_BYTES,
-                       d.stream, a);
+    // NB = 1 measured faster than NB = 2 on every configuration: vector-ALU and matrix-core
+    // instructions of a SIMD issue serially, so hiding LDS and barrier latency with a second
+    // wavefront pays more than halving the LDS traffic
+    hipLaunchKernelGGL(prefix_attn_query_split_kernel<1>, grid, dim3(512), QS_LDS_BYTES, d.stream,
+                       a);
   } else {
     dim3 grid(p.H, (a.M + 63) / 64, p.np_split);
     hipLaunchKernelGGL(prefix_attn_token_split_kernel, grid, dim3(256), TS_LDS_BYTES, d.stream, a);

@@ -30,6 +30,12 @@ SMALL_CASES = {
                             suffix_max=330, seed=26),
     "batch_300": dict(batch=300, heads=16, q_len=1, prefix_len=200, suffix_min=0, suffix_max=40,
                       seed=28),
+    "nothing_visible": dict(batch=6, heads=16, q_len=3, prefix_len=0, suffix_min=0, suffix_max=4,
+                            seed=29),
+    "one_token_prefix": dict(batch=2, heads=16, q_len=1, prefix_len=1, suffix_min=0, suffix_max=1,
+                             seed=30),
+    "h64_kimi_like": dict(batch=3, heads=64, q_len=1, prefix_len=160, suffix_min=10, suffix_max=140,
+                          seed=31),
     "wide_batch": dict(batch=70, heads=16, q_len=1, prefix_len=130, suffix_min=0, suffix_max=70,
                        seed=27),
 }
