@@ -107,7 +107,16 @@ __global__ void __launch_bounds__(256, 1) absorb16_kernel(Absorb16Args a) {
 
   // ---- tile streaming into this wavefront's private slot: 32 latent rows + 4 rope groups
   char* slot = smem + wave * A16_TILE_BYTES;
+  // physical blocks of this wavefront's token range: one entry per lane, picked with v_readlane
+  // (ranges longer than 64 blocks fall back to a scalar load per tile)
   const int32_t* bt = a.block_table + (size_t)b * a.max_blocks;
+  const int first_blk = is_prefix ? 0 : t0 / a.block_size;
+  int bt_cache = 0;
+  if (!is_prefix) {
+    const int nblk_mine = (t1 - 1) / a.block_size - first_blk + 1;
+    bt_cache = (lane < nblk_mine) ? bt[first_blk + lane] : 0;
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(bt_cache)::"memory");
+  }
   const int lane_off0 = lane << 4, lane_off1 = (lane ^ 1) << 4;
   const int rope_ch = ((lane & 7) ^ ((lane >> 3) & 7)) << 4;
   auto issue_tile = [&](int tile, auto prefix_tag) __attribute__((always_inline)) {
@@ -118,7 +127,9 @@ __global__ void __launch_bounds__(256, 1) absorb16_kernel(Absorb16Args a) {
     if constexpr (PREFIX) {
       base = (const char*)a.pc + (size_t)tok0 * (D_L * 2);
     } else {
-      const int blk = scalar_load_i32(bt + __builtin_amdgcn_readfirstlane(tok0 / a.block_size));
+      const int bi = __builtin_amdgcn_readfirstlane(tok0 / a.block_size - first_blk);
+      const int blk = bi < 64 ? __builtin_amdgcn_readlane(bt_cache, bi)
+                              : scalar_load_i32(bt + first_blk + bi);
       base = (const char*)(a.pool + ((size_t)blk * a.block_size + tok0 % a.block_size) * D_ROW);
     }
     constexpr int row_bytes = PREFIX ? D_L * 2 : D_ROW * 2;

@@ -65,7 +65,8 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
   constexpr int MBW = 16 / NLP;  // 32-latent blocks owned by a wavefront
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int item = blockIdx.x, qg = blockIdx.y, b = blockIdx.z;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, g = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: transfer bookkeeping is SALU
   const int qb = wave % NQB, lp = wave / NQB;
   const int r_local = (qg * NQB + qb) * 32 + n;   // this lane's query row within the request
   const bool q_valid = r_local < a.R;
@@ -114,7 +115,17 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
   // ---- tile streaming: global -> LDS.  This wavefront moves latent rows wave, wave+4, ... and
   // the rope parts of rows 8*wave .. 8*wave+7.  All row arithmetic is wave-uniform; the only
   // per-lane terms are the two swizzled lane offsets and the rope lane's row / chunk.
+  // The physical blocks of this chunk are fetched once, one entry per lane (a chunk spans at most
+  // 64 blocks here, longer ones fall back to a scalar load per tile), and picked with v_readlane:
+  // no memory latency on the tile-issue path.
   const int32_t* bt = a.block_table + (size_t)b * a.max_blocks;
+  const int first_blk = is_prefix ? 0 : t0 / a.block_size;
+  int bt_cache = 0;
+  if (!is_prefix) {
+    const int nblk_chunk = (t1 - 1) / a.block_size - first_blk + 1;
+    bt_cache = (lane < nblk_chunk) ? bt[first_blk + lane] : 0;
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(bt_cache)::"memory");
+  }
   const int lane_off0 = lane << 4, lane_off1 = (lane ^ 1) << 4;
   const int rope_row = 8 * wave + (lane >> 3);
   const int rope_ch = ((lane & 7) ^ ((lane >> 3) & 7)) << 4;
@@ -126,7 +137,9 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
     if constexpr (PREFIX) {
       base = (const char*)a.pc + (size_t)tok0 * (D_L * 2);
     } else {
-      const int blk = scalar_load_i32(bt + tok0 / a.block_size);
+      const int bi = __builtin_amdgcn_readfirstlane(tok0 / a.block_size - first_blk);
+      const int blk = bi < 64 ? __builtin_amdgcn_readlane(bt_cache, bi)
+                              : scalar_load_i32(bt + first_blk + bi);
       base = (const char*)(a.pool + ((size_t)blk * a.block_size + tok0 % a.block_size) * D_ROW);
     }
     constexpr int row_bytes = PREFIX ? D_L * 2 : D_ROW * 2;
@@ -196,21 +209,31 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
 #pragma unroll
     for (int v = 0; v < 16; v++) sacc[v] = 0.f;
     {
-      // 9 groups of 4 k-steps; the last group is the rope part
-      bf16x8 f[2][4];
-      static_for<4>([&](auto j) { f[0][j] = lds_read_b128<32 * decltype(j)::value>(sa); });
+      // 9 groups of 4 k-steps (the last one is the rope part); three fragment buffers in
+      // rotation keep two groups of LDS reads in flight behind the one feeding the MFMAs
+      bf16x8 f[3][4];
+      auto rd = [&](auto gsel, auto dsel) __attribute__((always_inline)) {
+        constexpr int G = decltype(gsel)::value;
+        constexpr int D = decltype(dsel)::value;
+        if constexpr (G < 8) {
+          static_for<4>([&](auto j) {
+            f[D][j] = lds_read_b128<32 * (4 * G + decltype(j)::value)>(sa);
+          });
+        } else {
+          static_for<4>([&](auto j) {
+            f[D][j] = lds_read_b128<0>(tbase + r_off[decltype(j)::value]);
+          });
+        }
+      };
+      rd(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+      rd(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
       static_for<9>([&](auto grp) {
         constexpr int G = decltype(grp)::value;
-        constexpr int cur = G & 1, nxt = cur ^ 1;
-        if constexpr (G + 1 < 8) {
-          static_for<4>([&](auto j) {
-            f[nxt][j] = lds_read_b128<32 * (4 * (G + 1) + decltype(j)::value)>(sa);
-          });
-          lgkm_wait<4>(f[cur][0], f[cur][1], f[cur][2], f[cur][3]);
-        } else if constexpr (G + 1 == 8) {
-          static_for<4>([&](auto j) {
-            f[nxt][j] = lds_read_b128<0>(tbase + r_off[decltype(j)::value]);
-          });
+        constexpr int cur = G % 3;
+        if constexpr (G + 2 < 9) {
+          rd(std::integral_constant<int, G + 2>{}, std::integral_constant<int, (G + 2) % 3>{});
+          lgkm_wait<8>(f[cur][0], f[cur][1], f[cur][2], f[cur][3]);
+        } else if constexpr (G + 1 < 9) {
           lgkm_wait<4>(f[cur][0], f[cur][1], f[cur][2], f[cur][3]);
         } else {
           lgkm_wait<0>(f[cur][0], f[cur][1], f[cur][2], f[cur][3]);
