@@ -99,7 +99,15 @@ def main():
         sys.exit(1)
     T.lib()  # fail loudly if the HIP library is not built
     dev = torch.device("cuda:0")
-    spec = W.CONFIGS[args.workload]
+    if args.workload in W.CONFIGS:
+        spec = W.CONFIGS[args.workload]
+    else:
+        # ad-hoc shape: "B=128,H=64,Ls=4096,Ln=512[,Lmax=..][,Sq=1][,seed=7]" (bf16, 64-token blocks)
+        kv = dict(item.split("=") for item in args.workload.split(","))
+        ln = int(kv.get("Ln", 512))
+        spec = W.WorkloadSpec(args.workload, "bf16", int(kv["B"]), int(kv.get("H", 128)),
+                              int(kv.get("Sq", 1)), int(kv.get("Ls", 4096)), ln,
+                              int(kv.get("Lmax", ln)), seed=int(kv.get("seed", 7)))
     t0 = time.perf_counter()
     wl = W.make_workload(spec, poison=True)
     gen_s = time.perf_counter() - t0

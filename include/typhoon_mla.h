@@ -53,7 +53,9 @@ typedef enum {
 typedef enum {
   TMLA_MODE_MIXED = 0,       /* Algorithm 1: naive prefix + absorb suffix + LSE combine      */
   TMLA_MODE_NAIVE_ONLY = 1,  /* Table 1 "Naive": expanded K/V for prefix and suffix           */
-  TMLA_MODE_ABSORB_ONLY = 2  /* Table 1 "Absorb": latent cache for prefix and suffix         */
+  TMLA_MODE_ABSORB_ONLY = 2, /* Table 1 "Absorb": latent cache for prefix and suffix         */
+  TMLA_MODE_AUTO = 3         /* Section 3.1 "Fall-back to Absorb": mixed when batch*q_len reaches
+                                the break-even batch of Section 3.2, absorb_only below it       */
 } tmla_mode;
 
 typedef enum { TMLA_BF16 = 0, TMLA_FP32 = 1 } tmla_dtype;
@@ -99,6 +101,16 @@ int typhoon_mla_expand_pool(const tmla_dims* dims, int32_t num_blocks, int32_t b
                             const void* suffix_pool, const void* w_uk, const void* w_uv,
                             void* suffix_k_pool, void* suffix_v_pool, void* stream);
 
+/*
+ * Break-even batch size B_theta of Section 3.2, (D_qk + D_v) / (q_len (2 D_l + D_r)) * T / M, with
+ * the throughput T of this library's absorb kernel over a shared prefix and the bandwidth M of its
+ * naive prefix kernel as measured on MI355X (about 300 TFLOP/s and 5 TB/s, giving 17.6 / q_len; the
+ * measured cross-over at prefix 4096 / suffix 512 lies between batch 4 and 16).  The environment
+ * variable TMLA_AUTO_BATCH_THRESHOLD overrides it.  TMLA_MODE_AUTO uses mixed when
+ * batch >= this value.
+ */
+double typhoon_mla_auto_batch_threshold(int32_t q_len);
+
 /* Scratch bytes typhoon_mla_decode needs for this problem size (a pure host function). */
 size_t typhoon_mla_decode_workspace_bytes(const tmla_dims* dims, int32_t mode, int32_t batch,
                                           int32_t q_len, int32_t prefix_len,
@@ -109,6 +121,7 @@ size_t typhoon_mla_decode_workspace_bytes(const tmla_dims* dims, int32_t mode, i
  *   q            in  [B, q_len, H, 192]  noPE 128 ++ RoPE 64
  *   prefix_k/_v  in  expanded prefix (mixed, naive_only; may be NULL otherwise or if prefix_len==0)
  *   prefix_ckv   in  [prefix_len, 512], prefix_krope [prefix_len, 64] (absorb_only; else may be NULL)
+ *                    TMLA_MODE_AUTO needs both forms of the prefix
  *   suffix_pool  in  [num_blocks, block_size, 576] latent rows (mixed, absorb_only)
  *   block_table  in  [B, max_blocks] int32 physical block of each logical suffix block;
  *                    entries beyond ceil(suffix_lens[b]/block_size) are never read

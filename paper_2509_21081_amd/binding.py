@@ -15,14 +15,16 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtyphoon
 
 TMLA_OK, TMLA_ERR_INVALID_ARG, TMLA_ERR_UNSUPPORTED, TMLA_ERR_WORKSPACE_TOO_SMALL, TMLA_ERR_HIP = \
     range(5)
-MODE_MIXED, MODE_NAIVE_ONLY, MODE_ABSORB_ONLY = 0, 1, 2
-MODES = {"mixed": MODE_MIXED, "naive_only": MODE_NAIVE_ONLY, "absorb_only": MODE_ABSORB_ONLY}
+MODE_MIXED, MODE_NAIVE_ONLY, MODE_ABSORB_ONLY, MODE_AUTO = 0, 1, 2, 3
+MODES = {"mixed": MODE_MIXED, "naive_only": MODE_NAIVE_ONLY, "absorb_only": MODE_ABSORB_ONLY,
+         "auto": MODE_AUTO}
 BF16, FP32 = 0, 1
 
 EXPORTS = [
     "typhoon_mla_status_string", "typhoon_mla_expanded_k_bytes", "typhoon_mla_expanded_v_bytes",
     "typhoon_mla_expand_prefix", "typhoon_mla_expand_pool", "typhoon_mla_decode_workspace_bytes",
     "typhoon_mla_decode", "typhoon_mla_combine_lse", "typhoon_mla_set_debug_flags",
+    "typhoon_mla_auto_batch_threshold",
 ]
 
 
@@ -73,6 +75,8 @@ def lib():
         L.typhoon_mla_combine_lse.restype = c_int
         L.typhoon_mla_combine_lse.argtypes = [c_int32, c_int64, c_int32, c_void_p, c_void_p,
                                               c_void_p, c_int32, c_void_p, c_void_p]
+        L.typhoon_mla_auto_batch_threshold.restype = ctypes.c_double
+        L.typhoon_mla_auto_batch_threshold.argtypes = [c_int32]
         L.typhoon_mla_set_debug_flags.restype = c_int
         L.typhoon_mla_set_debug_flags.argtypes = [c_int]
         _lib = L
@@ -108,6 +112,10 @@ def typhoon_mla_status_string(status):
 
 def typhoon_mla_set_debug_flags(flags):
     return lib().typhoon_mla_set_debug_flags(int(flags))
+
+
+def typhoon_mla_auto_batch_threshold(q_len=1):
+    return lib().typhoon_mla_auto_batch_threshold(int(q_len))
 
 
 def typhoon_mla_expanded_k_bytes(dims, num_tokens):

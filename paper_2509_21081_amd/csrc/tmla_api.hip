@@ -195,7 +195,8 @@ static int check_decode_sizes(const tmla_dims* dims, int mode, int batch, int q_
                               int prefix_len, int max_suffix_len) {
   const int st = check_dims(dims);
   if (st != TMLA_OK) return st;
-  if (mode != TMLA_MODE_MIXED && mode != TMLA_MODE_NAIVE_ONLY && mode != TMLA_MODE_ABSORB_ONLY)
+  if (mode != TMLA_MODE_MIXED && mode != TMLA_MODE_NAIVE_ONLY && mode != TMLA_MODE_ABSORB_ONLY &&
+      mode != TMLA_MODE_AUTO)
     return TMLA_ERR_INVALID_ARG;
   if (batch < 0 || q_len <= 0 || prefix_len < 0 || max_suffix_len < 0) return TMLA_ERR_INVALID_ARG;
   if (q_len > 8) return TMLA_ERR_UNSUPPORTED;
@@ -203,10 +204,28 @@ static int check_decode_sizes(const tmla_dims* dims, int mode, int batch, int q_
   return TMLA_OK;
 }
 
+// measured on MI355X: absorb attention over a shared prefix ~300 TFLOP/s, naive prefix ~5 TB/s
+static constexpr double AUTO_T_FLOPS = 300e12, AUTO_M_BYTES = 5e12;
+
+double typhoon_mla_auto_batch_threshold(int32_t q_len) {
+  const char* e = getenv("TMLA_AUTO_BATCH_THRESHOLD");
+  if (e && *e) return atof(e);
+  if (q_len <= 0) q_len = 1;
+  // Section 3.2: L_s H (D_qk+D_v) w / M = B S_q L_s H (2 D_l + D_r) 2 / T  with w = 2 bytes
+  return (double)(D_QK + D_V) / (q_len * (2.0 * D_L + D_R)) * AUTO_T_FLOPS / AUTO_M_BYTES;
+}
+
+static int resolve_auto(int mode, int batch, int q_len, int prefix_len) {
+  if (mode != TMLA_MODE_AUTO) return mode;
+  if (prefix_len == 0) return TMLA_MODE_MIXED;   // nothing to choose: both run the absorb suffix
+  return batch >= typhoon_mla_auto_batch_threshold(q_len) ? TMLA_MODE_MIXED : TMLA_MODE_ABSORB_ONLY;
+}
+
 size_t typhoon_mla_decode_workspace_bytes(const tmla_dims* dims, int32_t mode, int32_t batch,
                                           int32_t q_len, int32_t prefix_len,
                                           int32_t max_suffix_len) {
   if (check_decode_sizes(dims, mode, batch, q_len, prefix_len, max_suffix_len) != TMLA_OK) return 0;
+  mode = resolve_auto(mode, batch, q_len, prefix_len);
   Plan p;
   // the plan rounds suffix chunks to the paged block size; 128 covers both supported sizes
   make_plan(dims, mode, batch, q_len, prefix_len, max_suffix_len, 128, &p);
@@ -230,6 +249,11 @@ int typhoon_mla_decode(const tmla_dims* dims, int32_t mode, int32_t batch, int32
   if ((int64_t)max_blocks * block_size < max_suffix_len) return TMLA_ERR_INVALID_ARG;
   if (batch == 0) return TMLA_OK;
   if (!q || !out || !suffix_lens) return TMLA_ERR_INVALID_ARG;
+  if (mode == TMLA_MODE_AUTO) {
+    if (prefix_len > 0 && (!prefix_k || !prefix_v || !prefix_ckv || !prefix_krope))
+      return TMLA_ERR_INVALID_ARG;
+    mode = resolve_auto(mode, batch, q_len, prefix_len);
+  }
   const bool need_naive_prefix = prefix_len > 0 && mode != TMLA_MODE_ABSORB_ONLY;
   const bool need_latent_prefix = prefix_len > 0 && mode == TMLA_MODE_ABSORB_ONLY;
   const bool need_latent_suffix = max_suffix_len > 0 && mode != TMLA_MODE_NAIVE_ONLY;

@@ -23,7 +23,7 @@ def run_library(wl, mode, device, expanded=None, flags=0):
     try:
         pk = pv = sk = sv = None
         L_s = wl.spec.prefix_len
-        if mode in ("mixed", "naive_only") and L_s > 0:
+        if mode in ("mixed", "naive_only", "auto") and L_s > 0:
             pk, pv = T.typhoon_mla_expand_prefix(dims, d.prefix_ckv, d.prefix_krope, d.w_uk, d.w_uv)
         if mode == "naive_only":
             sk, sv = T.typhoon_mla_expand_pool(dims, d.pool, d.w_uk, d.w_uv)

@@ -148,3 +148,12 @@ def test_modes_agree_with_each_other(gpu_device):
         np.testing.assert_allclose(outs[m][0], outs["mixed"][0], atol=1e-2, rtol=2e-2)
         fin = np.isfinite(outs["mixed"][1])
         np.testing.assert_allclose(outs[m][1][fin], outs["mixed"][1][fin], atol=2e-3)
+
+
+@pytest.mark.parametrize("case", ["ragged_h16", "wide_batch"])
+def test_auto_mode_matches_oracle(case, gpu_device):
+    # batch 3 is below the break-even batch (absorb_only is chosen), batch 70 above it (mixed)
+    wl, (ref, ref_lse) = _workload_and_ref(case, "bf16")
+    print(f"auto mode case={case}", flush=True)
+    got, got_lse = Hh.run_library(wl, "auto", gpu_device)
+    Hh.assert_parity(got, got_lse, ref, ref_lse, "bf16", f"{case}/auto")

@@ -136,3 +136,21 @@ def test_combine_validation():
     assert L.typhoon_mla_combine_lse(2, 4, 128, None, one, one, 1, None, None) == \
         T.TMLA_ERR_INVALID_ARG
     assert L.typhoon_mla_combine_lse(2, 0, 128, None, None, None, 1, None, None) == T.TMLA_OK
+
+
+def test_auto_mode_threshold_follows_break_even_formula():
+    from paper_2509_21081_amd import cost_model as C
+    t1 = T.typhoon_mla_auto_batch_threshold(1)
+    # Section 3.2 closed form with the library's measured T = 300 TFLOP/s and M = 5 TB/s
+    assert abs(t1 - C.batch_threshold(300e12, 5e12, 1)) < 1e-9
+    assert abs(T.typhoon_mla_auto_batch_threshold(2) - t1 / 2) < 1e-9
+    L = T.lib()
+    d = _dims()
+    # auto needs both forms of the prefix
+    assert _decode(L, d, mode=3, prefix_ckv=None) == T.TMLA_ERR_INVALID_ARG
+    assert _decode(L, d, mode=3, prefix_k=None) == T.TMLA_ERR_INVALID_ARG
+    assert _decode(L, d, mode=4) == T.TMLA_ERR_INVALID_ARG
+    big = T.typhoon_mla_decode_workspace_bytes(d, T.MODE_AUTO, 64, 1, 4096, 512)
+    assert big == T.typhoon_mla_decode_workspace_bytes(d, T.MODE_MIXED, 64, 1, 4096, 512)
+    small = T.typhoon_mla_decode_workspace_bytes(d, T.MODE_AUTO, 2, 1, 4096, 512)
+    assert small == T.typhoon_mla_decode_workspace_bytes(d, T.MODE_ABSORB_ONLY, 2, 1, 4096, 512)
