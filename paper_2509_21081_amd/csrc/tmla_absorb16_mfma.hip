@@ -30,7 +30,7 @@ struct Absorb16Args {
   const __bf16* pool;        // [num_blocks, block_size, 576]
   const int32_t* block_table;
   const int32_t* lens;
-  float* lat_o;              // [n_lat, rows, 512]
+  __bf16* lat_o;             // [n_lat, rows, 512]
   float* lat_lse;            // [n_lat, rows]
   int Sq, H, R, Ls, ap_chunks, ap_chunk, as_chunks, as_chunk, ap_groups, max_blocks, block_size;
   int64_t rows;
@@ -88,7 +88,7 @@ __global__ void __launch_bounds__(256, 1) absorb16_kernel(Absorb16Args a) {
   }
   if (wave >= nparts) return;   // no barriers below: wavefronts are independent
   const int item = first_item + wave;
-  float* o_dst = a.lat_o + ((size_t)item * a.rows + row) * D_L + 4 * q4;
+  __bf16* o_dst = a.lat_o + ((size_t)item * a.rows + row) * D_L + 4 * q4;
   float* l_dst = a.lat_lse + (size_t)item * a.rows + row;
   const int span = max(0, span1 - span0);
   const int part = ((span + nparts - 1) / nparts + 31) & ~31;   // tokens per wavefront, tile aligned
@@ -310,8 +310,10 @@ __global__ void __launch_bounds__(256, 1) absorb16_kernel(Absorb16Args a) {
     const float inv = 1.f / lt;
 #pragma unroll
     for (int mb = 0; mb < 32; mb++) {
-      float4 w = make_float4(o[mb][0] * inv, o[mb][1] * inv, o[mb][2] * inv, o[mb][3] * inv);
-      *(float4*)(o_dst + 16 * mb) = w;
+      bf16x4 w;
+#pragma unroll
+      for (int e = 0; e < 4; e++) w[e] = (__bf16)(o[mb][e] * inv);
+      *(bf16x4*)(o_dst + 16 * mb) = w;
     }
     if (q4 == 0) *l_dst = (m + fast_log2(lt)) * LN2;
   } else if (q4 == 0) {
@@ -328,7 +330,7 @@ int mfma_absorb16_attention(const Plan& p, const DecodeArgs& d) {
   a.pool = (const __bf16*)d.suffix_pool;
   a.block_table = d.block_table;
   a.lens = d.suffix_lens;
-  a.lat_o = (float*)(d.ws + p.off_lat_o);
+  a.lat_o = (__bf16*)(d.ws + p.off_lat_o);
   a.lat_lse = (float*)(d.ws + p.off_lat_lse);
   a.Sq = p.Sq; a.H = p.H; a.R = p.Sq * p.H; a.Ls = p.Ls;
   a.ap_chunks = p.ap_chunks; a.ap_chunk = p.ap_chunk;

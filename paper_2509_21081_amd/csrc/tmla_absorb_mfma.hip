@@ -35,7 +35,7 @@ struct AbsorbArgs {
   const __bf16* pool;        // [num_blocks, block_size, 576]
   const int32_t* block_table;
   const int32_t* lens;
-  float* lat_o;              // [n_lat, rows, 512]
+  __bf16* lat_o;             // [n_lat, rows, 512]
   float* lat_lse;            // [n_lat, rows]
   int Sq, H, R, Ls, ap_chunks, ap_chunk, as_chunk, max_blocks, block_size;
   int64_t rows;
@@ -58,6 +58,39 @@ constexpr int AB_TILE_BYTES = AB_MAIN_BYTES + 32 * 128;   // 37888
 constexpr int AB_DMA_PER_WAVE = 9;                 // 8 latent rows + 1 rope group per wavefront
 constexpr int AB_NSLOT = 4;                        // tiles resident in LDS (3 in flight + 1 in use)
 constexpr int AB_LDS_BYTES = AB_NSLOT * AB_TILE_BYTES;
+
+// Where the 32 rows of one LDS tile come from: latent part and rope part of row i start at
+// lat + i * lat_stride and rope + i * rope_stride; rows past `last` repeat row `last`.
+struct RowSrc {
+  const char* lat;
+  const char* rope;
+  int lat_stride, rope_stride, last;
+};
+
+// Per-lane constants of the tile transfers (see the tile layout above).
+struct DmaLane {
+  int wave, off0, off1, rope_row, rope_ch;
+};
+
+// K-th of the nine transfers with which one wavefront contributes to a tile: latent rows
+// wave, wave + 4, ..., wave + 28 (K < 8), then the rope parts of rows 8*wave .. 8*wave+7 (K = 8).
+// All row arithmetic is wave-uniform; the only per-lane terms are the swizzled lane offsets.
+template <int K>
+__device__ __attribute__((always_inline)) inline void issue_part(const RowSrc& s, char* dst,
+                                                                 const DmaLane& d) {
+  if constexpr (K < 8) {
+    const int r = d.wave + 4 * K;          // (r >> 2) & 1 == K & 1
+    const int rr = min(r, s.last);
+    dma16(s.lat + (size_t)rr * s.lat_stride + ((K & 1) ? d.off1 : d.off0), dst + r * AB_ROW_BYTES);
+  } else {
+    const int rr = min(d.rope_row, s.last);
+    dma16(s.rope + (size_t)rr * s.rope_stride + d.rope_ch, dst + AB_MAIN_BYTES + d.wave * 1024);
+  }
+}
+__device__ __attribute__((always_inline)) inline void issue_all(const RowSrc& s, char* dst,
+                                                                const DmaLane& d) {
+  static_for<AB_DMA_PER_WAVE>([&](auto k) { issue_part<decltype(k)::value>(s, dst, d); });
+}
 
 template <int NQB>
 __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
@@ -86,7 +119,7 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
     const int s = q_valid ? r_local / a.H : 0;
     vis_q = max(0, min(len, len - a.Sq + s + 1));
   }
-  float* o_dst = a.lat_o + ((size_t)item * a.rows + row) * D_L;
+  __bf16* o_dst = a.lat_o + ((size_t)item * a.rows + row) * D_L;
   float* l_dst = a.lat_lse + (size_t)item * a.rows + row;
   if (t1 <= t0) {   // empty chunk (workgroup-uniform)
     if (q_valid && lp == 0 && g == 0) *l_dst = -INFINITY;
@@ -94,27 +127,7 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
   }
   const int ntile = (t1 - t0 + 31) / 32;
 
-  // ---- absorbed query fragments (B operand): 36 k-steps of 16
-  bf16x8 qf[36];
-  {
-    const __bf16* qp = a.qabs + row * D_ROW + 8 * g;
-#pragma unroll
-    for (int ks = 0; ks < 36; ks++) {
-      bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-      qf[ks] = q_valid ? *(const bf16x8*)(qp + 16 * ks) : z;
-    }
-  }
-
-  // the fragments must be resident before the streamed loads start, so that no wait on them
-  // (which would also drain the tile prefetch) is needed inside the loop
-#pragma unroll
-  for (int ks = 0; ks < 36; ks += 4)
-    asm volatile("s_waitcnt vmcnt(0)"
-                 : "+v"(qf[ks]), "+v"(qf[ks + 1]), "+v"(qf[ks + 2]), "+v"(qf[ks + 3])::"memory");
-
-  // ---- tile streaming: global -> LDS.  This wavefront moves latent rows wave, wave+4, ... and
-  // the rope parts of rows 8*wave .. 8*wave+7.  All row arithmetic is wave-uniform; the only
-  // per-lane terms are the two swizzled lane offsets and the rope lane's row / chunk.
+  // ---- tile streaming: global -> LDS.
   // The physical blocks of this chunk are fetched once, one entry per lane (a chunk spans at most
   // 64 blocks here, longer ones fall back to a scalar load per tile), and picked with v_readlane:
   // no memory latency on the tile-issue path.
@@ -126,44 +139,33 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
     bt_cache = (lane < nblk_chunk) ? bt[first_blk + lane] : 0;
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(bt_cache)::"memory");
   }
-  const int lane_off0 = lane << 4, lane_off1 = (lane ^ 1) << 4;
-  const int rope_row = 8 * wave + (lane >> 3);
-  const int rope_ch = ((lane & 7) ^ ((lane >> 3) & 7)) << 4;
-  auto issue_tile = [&](int tile, auto prefix_tag) __attribute__((always_inline)) {
-    constexpr bool PREFIX = decltype(prefix_tag)::value;
+  DmaLane dl;
+  dl.wave = wave;
+  dl.off0 = lane << 4;
+  dl.off1 = (lane ^ 1) << 4;
+  dl.rope_row = 8 * wave + (lane >> 3);
+  dl.rope_ch = ((lane & 7) ^ ((lane >> 3) & 7)) << 4;
+  auto tile_src = [&](int tile) __attribute__((always_inline)) {
+    RowSrc s;
     const int tok0 = t0 + tile * 32;
-    const int last = t1 - 1 - tok0;      // last valid row of this tile (>= 0)
-    const char* base;                    // first latent row of the tile
-    if constexpr (PREFIX) {
-      base = (const char*)a.pc + (size_t)tok0 * (D_L * 2);
+    s.last = t1 - 1 - tok0;              // last valid row of this tile (>= 0)
+    if (is_prefix) {
+      s.lat = (const char*)a.pc + (size_t)tok0 * (D_L * 2);
+      s.rope = (const char*)a.pr + (size_t)tok0 * (D_R * 2);
+      s.lat_stride = D_L * 2;
+      s.rope_stride = D_R * 2;
     } else {
       const int bi = __builtin_amdgcn_readfirstlane(tok0 / a.block_size - first_blk);
       const int blk = bi < 64 ? __builtin_amdgcn_readlane(bt_cache, bi)
                               : scalar_load_i32(bt + first_blk + bi);
-      base = (const char*)(a.pool + ((size_t)blk * a.block_size + tok0 % a.block_size) * D_ROW);
+      s.lat = (const char*)(a.pool + ((size_t)blk * a.block_size + tok0 % a.block_size) * D_ROW);
+      s.rope = s.lat + D_L * 2;
+      s.lat_stride = s.rope_stride = D_ROW * 2;
     }
-    constexpr int row_bytes = PREFIX ? D_L * 2 : D_ROW * 2;
-    char* dst = smem + (tile % AB_NSLOT) * AB_TILE_BYTES;
-#pragma unroll
-    for (int k = 0; k < 8; k++) {
-      const int r = wave + 4 * k;
-      const int rr = min(r, last);
-      const int loff = ((r >> 2) & 1) ? lane_off1 : lane_off0;   // (r >> 2) & 1 == k & 1
-      dma16(base + (size_t)rr * row_bytes + loff, dst + r * AB_ROW_BYTES);
-    }
-    {
-      const int rr = min(rope_row, last);
-      const char* src;
-      if constexpr (PREFIX)
-        src = (const char*)a.pr + (size_t)(tok0 + rr) * (D_R * 2) + rope_ch;
-      else
-        src = base + (size_t)rr * row_bytes + D_L * 2 + rope_ch;
-      dma16(src, dst + AB_MAIN_BYTES + wave * 1024);
-    }
+    return s;
   };
-  auto issue = [&](int tile) __attribute__((always_inline)) {
-    if (is_prefix) issue_tile(tile, std::true_type{});
-    else issue_tile(tile, std::false_type{});
+  auto slot_ptr = [&](int tile) __attribute__((always_inline)) {
+    return smem + (tile % AB_NSLOT) * AB_TILE_BYTES;
   };
 
   // per-lane LDS byte offsets inside a tile
@@ -182,16 +184,61 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
                          ((2 * (j16 & 1) + (((r16 & 3) >> 1) ^ g)) << 4) + 8 * (r16 & 1) +
                          64 * (lp * MBW);
 
+  // ---- absorbed query fragments (B operand): 36 k-steps of 16.
+  // The NQB blocks of 32 absorbed-query rows are staged like cache tiles (same transfers, same
+  // layout) in the last NQB ring slots, and every wavefront picks its block's fragments with the
+  // score-product read pattern: the rows are fetched once per workgroup with full 1 KiB
+  // transfers instead of once per wavefront with 32-byte pieces.  The first tiles of the chunk
+  // stream into the other slots meanwhile.
+  constexpr int NPRE = AB_NSLOT - NQB;   // tiles issued next to the query blocks
+  {
+    const int64_t req_row0 = (int64_t)b * a.R;
+#pragma unroll
+    for (int j = 0; j < NQB; j++) {
+      const int blk_row0 = (qg * NQB + j) * 32;
+      RowSrc qs;
+      qs.last = min(31, a.R - 1 - blk_row0);
+      int64_t first = req_row0 + blk_row0;
+      if (qs.last < 0) {   // block entirely past the request's rows: any valid row will do
+        qs.last = 0;
+        first = req_row0 + a.R - 1;
+      }
+      qs.lat = (const char*)(a.qabs + first * D_ROW);
+      qs.rope = qs.lat + D_L * 2;
+      qs.lat_stride = qs.rope_stride = D_ROW * 2;
+      issue_all(qs, smem + (NPRE + j) * AB_TILE_BYTES, dl);
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < NPRE; t++)
+    if (t < ntile) issue_all(tile_src(t), slot_ptr(t), dl);
+  {
+    const int pre = min(ntile, NPRE);    // tiles in flight behind the query blocks
+    if (pre >= 3) vm_wait<3 * AB_DMA_PER_WAVE>();
+    else if (pre == 2) vm_wait<2 * AB_DMA_PER_WAVE>();
+    else vm_wait<AB_DMA_PER_WAVE>();
+  }
+  raw_barrier();
+  bf16x8 qf[36];
+  {
+    const uint32_t qa = smem_base + (NPRE + qb) * AB_TILE_BYTES;
+    static_for<32>([&](auto ks) { qf[decltype(ks)::value] = lds_read_b128<32 * decltype(ks)::value>(qa + s_off); });
+    static_for<4>([&](auto k) { qf[32 + decltype(k)::value] = lds_read_b128<0>(qa + r_off[decltype(k)::value]); });
+#pragma unroll
+    for (int ks = 0; ks < 36; ks += 4)
+      lgkm_wait<0>(qf[ks], qf[ks + 1], qf[ks + 2], qf[ks + 3]);
+  }
+  raw_barrier();   // the query slots may now be overwritten by tiles
+#pragma unroll
+  for (int t = NPRE; t < AB_NSLOT - 1; t++)
+    if (t < ntile) issue_all(tile_src(t), slot_ptr(t), dl);
+
   f32x16 o[MBW];
 #pragma unroll
   for (int mb = 0; mb < MBW; mb++)
 #pragma unroll
     for (int v = 0; v < 16; v++) o[mb][v] = 0.f;
   float m = -INFINITY, l = 0.f;
-
-#pragma unroll
-  for (int t = 0; t < AB_NSLOT - 1; t++)
-    if (t < ntile) issue(t);
 
   for (int tile = 0; tile < ntile; tile++) {
     // this wavefront's transfers of `tile` are complete once at most the transfers of the
@@ -201,7 +248,19 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
     else if (ahead == 1) vm_wait<AB_DMA_PER_WAVE>();
     else vm_wait<0>();
     raw_barrier();   // everyone's part of `tile` has landed; everyone is done with tile - 1
-    if (tile + AB_NSLOT - 1 < ntile) issue(tile + AB_NSLOT - 1);
+    // The four wavefronts run the same instruction stream; leaving the barrier together they
+    // would present their transfers and LDS reads at the same cycle and queue behind each
+    // other.  A skew of 32 cycles per wavefront (one MFMA) keeps them apart.
+    if (wave & 1) asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    if (wave & 2) asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    // the tile three ahead goes into the slot freed by the barrier; its transfers are spread
+    // over the score product (one per group of four MFMAs) so that the wavefront never sits
+    // behind a full memory-instruction queue
+    const int pf = tile + AB_NSLOT - 1;
+    const bool do_pf = pf < ntile;
+    RowSrc pf_src;
+    if (do_pf) pf_src = tile_src(pf);
+    char* pf_dst = slot_ptr(pf);
 
     const uint32_t tbase = smem_base + (tile % AB_NSLOT) * AB_TILE_BYTES;
     const uint32_t sa = tbase + s_off;
@@ -241,6 +300,7 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
         static_for<4>([&](auto j) {
           sacc = mfma32(f[cur][j], qf[4 * G + decltype(j)::value], sacc);
         });
+        if (do_pf) issue_part<G>(pf_src, pf_dst, dl);
       });
     }
     const int limit = min(32, vis_q - (t0 + tile * 32));
@@ -297,9 +357,10 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
     for (int mb = 0; mb < MBW; mb++)
 #pragma unroll
       for (int v4 = 0; v4 < 4; v4++) {
-        float4 w = make_float4(o[mb][4 * v4] * inv, o[mb][4 * v4 + 1] * inv,
-                               o[mb][4 * v4 + 2] * inv, o[mb][4 * v4 + 3] * inv);
-        *(float4*)(o_dst + 32 * (lp * MBW + mb) + 8 * v4 + 4 * g) = w;
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; e++) w[e] = (__bf16)(o[mb][4 * v4 + e] * inv);
+        *(bf16x4*)(o_dst + 32 * (lp * MBW + mb) + 8 * v4 + 4 * g) = w;
       }
     if (lp == 0 && g == 0) *l_dst = (m + fast_log2(lt)) * LN2;
   } else if (lp == 0 && g == 0) {
@@ -317,7 +378,7 @@ int mfma_absorb_attention(const Plan& p, const DecodeArgs& d) {
   a.pool = (const __bf16*)d.suffix_pool;
   a.block_table = d.block_table;
   a.lens = d.suffix_lens;
-  a.lat_o = (float*)(d.ws + p.off_lat_o);
+  a.lat_o = (__bf16*)(d.ws + p.off_lat_o);
   a.lat_lse = (float*)(d.ws + p.off_lat_lse);
   a.Sq = p.Sq; a.H = p.H; a.R = p.Sq * p.H; a.Ls = p.Ls;
   a.ap_chunks = p.ap_chunks; a.ap_chunk = p.ap_chunk; a.as_chunk = p.as_chunk;

@@ -98,7 +98,7 @@ int make_plan(const tmla_dims* dims, int mode, int B, int Sq, int Ls, int max_su
   p->off_qabs = off;      off = align_up(off + (p->n_lat ? (size_t)p->rows * D_ROW * esz : 0), 256);
   p->off_naive_o = off;   off = align_up(off + (size_t)p->n_naive * p->rows * D_V * 4, 256);
   p->off_naive_lse = off; off = align_up(off + (size_t)p->n_naive * p->rows * 4, 256);
-  p->off_lat_o = off;     off = align_up(off + (size_t)p->n_lat * p->rows * D_L * 4, 256);
+  p->off_lat_o = off;     off = align_up(off + (size_t)p->n_lat * p->rows * D_L * esz, 256);
   p->off_lat_lse = off;   off = align_up(off + (size_t)p->n_lat * p->rows * 4, 256);
   p->total = off + 256;
   return TMLA_OK;

@@ -109,77 +109,16 @@ int mfma_query_absorb(const Plan& p, const DecodeArgs& d) {
 constexpr int FIN_MAX_LAT = 64;  // latent partials per row supported by the weight table in LDS
 
 struct FinalizeArgs {
-  const float* naive_o; const float* naive_lse; const float* lat_o; const float* lat_lse;
+  const float* naive_o; const float* naive_lse; const __bf16* lat_o; const float* lat_lse;
   const __bf16* w_uv; __bf16* out; float* lse_out;
   int M, H, n_naive, n_lat;
   int64_t rows;
 };
 
-__global__ void __launch_bounds__(256) finalize_kernel(FinalizeArgs a) {
-  __shared__ float wtab[FIN_MAX_LAT][32];    // normalised merge weight of each latent partial
-  __shared__ float red[4][4][16][64];        // [wavefront][value block][acc register][lane]
-  const int h = blockIdx.x, qb = blockIdx.y;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, g = lane >> 5;
-  const int qi = qb * 32 + n;
-  const bool valid = qi < a.M;
-  const size_t row = valid ? (size_t)qi * a.H + h : 0;
-
-  float l_a = -INFINITY;
-  float oa[16];   // this wavefront's 32 value columns of O_A after the cross-wavefront sum
-#pragma unroll
-  for (int v = 0; v < 16; v++) oa[v] = 0.f;
-  if (a.n_lat > 0) {
-    float mx = -INFINITY;
-    for (int i = 0; i < a.n_lat; i++) mx = fmaxf(mx, a.lat_lse[(size_t)i * a.rows + row]);
-    float z = 0.f;
-    if (mx > -INFINITY)
-      for (int i = 0; i < a.n_lat; i++) z += __expf(a.lat_lse[(size_t)i * a.rows + row] - mx);
-    const float inv = (z > 0.f && valid) ? 1.f / z : 0.f;
-    // every wavefront computes the same weights; wavefront 0 publishes them
-    if (wave == 0 && g == 0)
-      for (int i = 0; i < a.n_lat; i++)
-        wtab[i][n] = (inv > 0.f) ? __expf(a.lat_lse[(size_t)i * a.rows + row] - mx) * inv : 0.f;
-    if (z > 0.f && valid) l_a = mx + __logf(z);
-    __syncthreads();
-
-    f32x16 acc[4];
-#pragma unroll
-    for (int mb = 0; mb < 4; mb++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) acc[mb][v] = 0.f;
-    const __bf16* wp = a.w_uv + ((size_t)h * D_V + n) * D_L + 8 * g + 128 * wave;
-    const float* lp = a.lat_o + row * D_L + 8 * g + 128 * wave;
-    for (int ks = 0; ks < 8; ks++) {
-      float m8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      for (int i = 0; i < a.n_lat; i++) {
-        const float w = wtab[i][n];
-        if (w > 0.f) {
-          const float4 x0 = *(const float4*)(lp + (size_t)i * a.rows * D_L + 16 * ks);
-          const float4 x1 = *(const float4*)(lp + (size_t)i * a.rows * D_L + 16 * ks + 4);
-          m8[0] += w * x0.x; m8[1] += w * x0.y; m8[2] += w * x0.z; m8[3] += w * x0.w;
-          m8[4] += w * x1.x; m8[5] += w * x1.y; m8[6] += w * x1.z; m8[7] += w * x1.w;
-        }
-      }
-      bf16x8 bfrag;
-#pragma unroll
-      for (int e = 0; e < 8; e++) bfrag[e] = (__bf16)m8[e];
-#pragma unroll
-      for (int mb = 0; mb < 4; mb++) {
-        const bf16x8 afrag = *(const bf16x8*)(wp + (size_t)(32 * mb) * D_L + 16 * ks);
-        acc[mb] = mfma32(afrag, bfrag, acc[mb]);
-      }
-    }
-#pragma unroll
-    for (int mb = 0; mb < 4; mb++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) red[wave][mb][v][lane] = acc[mb][v];
-    __syncthreads();
-#pragma unroll
-    for (int v = 0; v < 16; v++)
-      oa[v] = red[0][wave][v][lane] + red[1][wave][v][lane] + red[2][wave][v][lane] +
-              red[3][wave][v][lane];
-  }
-  if (!valid) return;
+// Steps shared by both finalize kernels: merge O_A (LSE l_a, this wavefront's 32 value columns
+// in oa) with the naive partials, normalise, store.
+__device__ inline void finalize_tail(const FinalizeArgs& a, size_t row, int wave, int g, float l_a,
+                                     float (&oa)[16]) {
   // merge O_A (LSE l_a) with the naive partials; this wavefront owns value block `wave`
   float m2 = l_a;
   for (int i = 0; i < a.n_naive; i++) m2 = fmaxf(m2, a.naive_lse[(size_t)i * a.rows + row]);
@@ -221,20 +160,189 @@ __global__ void __launch_bounds__(256) finalize_kernel(FinalizeArgs a) {
   if (a.lse_out && wave == 0 && g == 0) a.lse_out[row] = m2 + __logf(z2);
 }
 
+__global__ void __launch_bounds__(256) finalize_kernel(FinalizeArgs a) {
+  __shared__ float wtab[FIN_MAX_LAT][32];    // normalised merge weight of each latent partial
+  __shared__ float red[4][4][16][64];        // [wavefront][value block][acc register][lane]
+  const int h = blockIdx.x, qb = blockIdx.y;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, g = lane >> 5;
+  const int qi = qb * 32 + n;
+  const bool valid = qi < a.M;
+  const size_t row = valid ? (size_t)qi * a.H + h : 0;
+
+  float l_a = -INFINITY;
+  float oa[16];   // this wavefront's 32 value columns of O_A after the cross-wavefront sum
+#pragma unroll
+  for (int v = 0; v < 16; v++) oa[v] = 0.f;
+  if (a.n_lat > 0) {
+    float mx = -INFINITY;
+    for (int i = 0; i < a.n_lat; i++) mx = fmaxf(mx, a.lat_lse[(size_t)i * a.rows + row]);
+    float z = 0.f;
+    if (mx > -INFINITY)
+      for (int i = 0; i < a.n_lat; i++) z += __expf(a.lat_lse[(size_t)i * a.rows + row] - mx);
+    const float inv = (z > 0.f && valid) ? 1.f / z : 0.f;
+    // every wavefront computes the same weights; wavefront 0 publishes them
+    if (wave == 0 && g == 0)
+      for (int i = 0; i < a.n_lat; i++)
+        wtab[i][n] = (inv > 0.f) ? __expf(a.lat_lse[(size_t)i * a.rows + row] - mx) * inv : 0.f;
+    if (z > 0.f && valid) l_a = mx + __logf(z);
+    __syncthreads();
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int mb = 0; mb < 4; mb++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[mb][v] = 0.f;
+    const __bf16* wp = a.w_uv + ((size_t)h * D_V + n) * D_L + 8 * g + 128 * wave;
+    const __bf16* lp = a.lat_o + row * D_L + 8 * g + 128 * wave;
+    for (int ks = 0; ks < 8; ks++) {
+      float m8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int i = 0; i < a.n_lat; i++) {
+        const float w = wtab[i][n];
+        if (w > 0.f) {
+          const bf16x8 x = *(const bf16x8*)(lp + (size_t)i * a.rows * D_L + 16 * ks);
+#pragma unroll
+          for (int e = 0; e < 8; e++) m8[e] += w * (float)x[e];
+        }
+      }
+      bf16x8 bfrag;
+#pragma unroll
+      for (int e = 0; e < 8; e++) bfrag[e] = (__bf16)m8[e];
+#pragma unroll
+      for (int mb = 0; mb < 4; mb++) {
+        const bf16x8 afrag = *(const bf16x8*)(wp + (size_t)(32 * mb) * D_L + 16 * ks);
+        acc[mb] = mfma32(afrag, bfrag, acc[mb]);
+      }
+    }
+#pragma unroll
+    for (int mb = 0; mb < 4; mb++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) red[wave][mb][v][lane] = acc[mb][v];
+    __syncthreads();
+#pragma unroll
+    for (int v = 0; v < 16; v++)
+      oa[v] = red[0][wave][v][lane] + red[1][wave][v][lane] + red[2][wave][v][lane] +
+              red[3][wave][v][lane];
+  }
+  if (!valid) return;
+  finalize_tail(a, row, wave, g, l_a, oa);
+}
+
+// Same computation for a compile-time number NL <= 4 of latent partials (the common case: the
+// suffix is rarely split more).  Nothing depends on anything but the loads, so all of them --
+// partial LSEs, weight fragments, latent partials -- are issued back to back and the kernel pays
+// one memory round trip instead of one per k-step; the merge weights live in registers.
+template <int NL>
+__global__ void __launch_bounds__(256) finalize_few_kernel(FinalizeArgs a) {
+  __shared__ float red[4][4][16][64];        // [wavefront][value block][acc register][lane]
+  const int h = blockIdx.x, qb = blockIdx.y;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, g = lane >> 5;
+  const int qi = qb * 32 + n;
+  const bool valid = qi < a.M;
+  const size_t row = valid ? (size_t)qi * a.H + h : 0;
+
+  float ll[NL];
+#pragma unroll
+  for (int i = 0; i < NL; i++) ll[i] = a.lat_lse[(size_t)i * a.rows + row];
+  const __bf16* wp = a.w_uv + ((size_t)h * D_V + n) * D_L + 8 * g + 128 * wave;
+  const __bf16* lp = a.lat_o + row * D_L + 8 * g + 128 * wave;
+  bf16x8 wf[8][4];
+#pragma unroll
+  for (int ks = 0; ks < 8; ks++)
+#pragma unroll
+    for (int mb = 0; mb < 4; mb++)
+      wf[ks][mb] = *(const bf16x8*)(wp + (size_t)(32 * mb) * D_L + 16 * ks);
+  bf16x8 x[NL][8];
+#pragma unroll
+  for (int i = 0; i < NL; i++)
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++)
+      x[i][ks] = *(const bf16x8*)(lp + (size_t)i * a.rows * D_L + 16 * ks);
+
+  // pin every load above this point: without it the scheduler sinks the loads next to their
+  // uses to save registers, and each k-step waits for its own round trip
+#pragma unroll
+  for (int ks = 0; ks < 8; ks++) {
+    asm volatile("" : "+v"(wf[ks][0]), "+v"(wf[ks][1]), "+v"(wf[ks][2]), "+v"(wf[ks][3]));
+#pragma unroll
+    for (int i = 0; i < NL; i++) asm volatile("" : "+v"(x[i][ks]));
+  }
+
+  // merge weights of the latent partials (a partial with LSE = -inf was never written)
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NL; i++) mx = fmaxf(mx, ll[i]);
+  float w[NL], z = 0.f;
+#pragma unroll
+  for (int i = 0; i < NL; i++) {
+    w[i] = (ll[i] > -INFINITY) ? __expf(ll[i] - mx) : 0.f;
+    z += w[i];
+  }
+  const bool any = z > 0.f && valid;
+  const float inv = any ? 1.f / z : 0.f;
+  const float l_a = any ? mx + __logf(z) : -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NL; i++) w[i] *= inv;
+
+  f32x16 acc[4];
+#pragma unroll
+  for (int mb = 0; mb < 4; mb++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) acc[mb][v] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 8; ks++) {
+    bf16x8 bfrag;
+    if constexpr (NL == 1) {
+      // a single partial is already the merged latent output (weight 1, or 0 if it saw nothing)
+      const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+      bfrag = w[0] > 0.f ? x[0][ks] : zero;
+    } else {
+      float m8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < NL; i++) {
+        const bool use = w[i] > 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; e++) m8[e] += use ? w[i] * (float)x[i][ks][e] : 0.f;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; e++) bfrag[e] = (__bf16)m8[e];
+    }
+#pragma unroll
+    for (int mb = 0; mb < 4; mb++) acc[mb] = mfma32(wf[ks][mb], bfrag, acc[mb]);
+  }
+#pragma unroll
+  for (int mb = 0; mb < 4; mb++)
+#pragma unroll
+    for (int v = 0; v < 16; v++) red[wave][mb][v][lane] = acc[mb][v];
+  __syncthreads();
+  float oa[16];
+#pragma unroll
+  for (int v = 0; v < 16; v++)
+    oa[v] = red[0][wave][v][lane] + red[1][wave][v][lane] + red[2][wave][v][lane] +
+            red[3][wave][v][lane];
+  if (!valid) return;
+  finalize_tail(a, row, wave, g, l_a, oa);
+}
+
 int mfma_finalize(const Plan& p, const DecodeArgs& d) {
   if (p.rows == 0) return TMLA_OK;
   if (p.n_lat > FIN_MAX_LAT) return TMLA_ERR_UNSUPPORTED;
   FinalizeArgs a;
   a.naive_o = (const float*)(d.ws + p.off_naive_o);
   a.naive_lse = (const float*)(d.ws + p.off_naive_lse);
-  a.lat_o = (const float*)(d.ws + p.off_lat_o);
+  a.lat_o = (const __bf16*)(d.ws + p.off_lat_o);
   a.lat_lse = (const float*)(d.ws + p.off_lat_lse);
   a.w_uv = (const __bf16*)d.w_uv;
   a.out = (__bf16*)d.out;
   a.lse_out = d.lse_out;
   a.M = p.B * p.Sq; a.H = p.H; a.n_naive = p.n_naive; a.n_lat = p.n_lat; a.rows = p.rows;
   dim3 grid(p.H, (a.M + 31) / 32);
-  hipLaunchKernelGGL(finalize_kernel, grid, dim3(256), 0, d.stream, a);
+  switch (p.n_lat) {
+    case 1: hipLaunchKernelGGL(finalize_few_kernel<1>, grid, dim3(256), 0, d.stream, a); break;
+    case 2: hipLaunchKernelGGL(finalize_few_kernel<2>, grid, dim3(256), 0, d.stream, a); break;
+    case 3: hipLaunchKernelGGL(finalize_few_kernel<3>, grid, dim3(256), 0, d.stream, a); break;
+    case 4: hipLaunchKernelGGL(finalize_few_kernel<4>, grid, dim3(256), 0, d.stream, a); break;
+    default: hipLaunchKernelGGL(finalize_kernel, grid, dim3(256), 0, d.stream, a);
+  }
   return TMLA_OK;
 }
 

@@ -38,10 +38,10 @@ __device__ inline float block_reduce_sum(float v, float* red) {
 
 // One softmax-attention pass of a single query vector (in LDS, fp32) over tokens [t0, t1).
 // kf(t, i): key element i of token t; vf(t, d): value element d.  Writes the normalised partial
-// output (DV floats) and its natural-log LSE; an empty range writes LSE = -inf only.
-template <int DK, int DV, typename KF, typename VF>
+// output (DV values of type OT) and its natural-log LSE; an empty range writes LSE = -inf only.
+template <int DK, int DV, typename OT, typename KF, typename VF>
 __device__ void attend_range(const float* q_lds, int t0, int t1, float scale, KF kf, VF vf,
-                             float* o_out, float* lse_out) {
+                             OT* o_out, float* lse_out) {
   __shared__ float p_lds[NT];
   __shared__ float red[NT];
   constexpr int VPT = DV / NT;
@@ -76,7 +76,7 @@ __device__ void attend_range(const float* q_lds, int t0, int t1, float scale, KF
   }
   if (t1 > t0) {
     const float inv = 1.f / l_run;
-    for (int c = 0; c < VPT; c++) o_out[tid + c * NT] = acc[c] * inv;
+    for (int c = 0; c < VPT; c++) o_out[tid + c * NT] = from_float<OT>(acc[c] * inv);
     if (tid == 0) *lse_out = m_run + logf(l_run);
   } else if (tid == 0) {
     *lse_out = -INFINITY;
@@ -183,7 +183,7 @@ simple_naive_kernel(Plan p, const T* __restrict__ q, const T* __restrict__ pk,
   if (chunk < p.np_split) {
     const int t0 = chunk * p.p_chunk, t1 = min(p.Ls, t0 + p.p_chunk);
     const int64_t ntok = p.Ls;
-    attend_range<D_QK, D_V>(
+    attend_range<D_QK, D_V, float>(
         q_lds, t0, t1, scale,
         [=](int t, int i) { return to_float(pk[ExpLayout<T>::k(h, ntok, t, i)]); },
         [=](int t, int d) { return to_float(pv[ExpLayout<T>::v(h, ntok, t, d)]); }, o_out, l_out);
@@ -193,7 +193,7 @@ simple_naive_kernel(Plan p, const T* __restrict__ q, const T* __restrict__ pk,
     const int t0 = min(vis, c * p.ns_chunk), t1 = min(vis, t0 + p.ns_chunk);
     const int32_t* bt = block_table + (size_t)b * max_blocks;
     auto phys = [=](int j) { return (int64_t)bt[j / block_size] * block_size + j % block_size; };
-    attend_range<D_QK, D_V>(
+    attend_range<D_QK, D_V, float>(
         q_lds, t0, t1, scale,
         [=](int j, int i) { return to_float(sk[ExpLayout<T>::k(h, pool_tokens, phys(j), i)]); },
         [=](int j, int d) { return to_float(sv[ExpLayout<T>::v(h, pool_tokens, phys(j), d)]); },
@@ -209,7 +209,7 @@ __global__ void __launch_bounds__(NT)
 simple_absorb_kernel(Plan p, const T* __restrict__ qabs, const T* __restrict__ pc,
                      const T* __restrict__ pr, const T* __restrict__ pool,
                      const int32_t* __restrict__ block_table, const int32_t* __restrict__ lens,
-                     int max_blocks, int block_size, float scale, float* __restrict__ lat_o,
+                     int max_blocks, int block_size, float scale, T* __restrict__ lat_o,
                      float* __restrict__ lat_lse) {
   __shared__ float q_lds[D_ROW];
   const int64_t row = blockIdx.x;
@@ -218,11 +218,11 @@ simple_absorb_kernel(Plan p, const T* __restrict__ qabs, const T* __restrict__ p
   const int b = (int)(row / ((int64_t)p.H * p.Sq));
   for (int i = threadIdx.x; i < D_ROW; i += NT) q_lds[i] = to_float(qabs[row * D_ROW + i]);
   __syncthreads();
-  float* o_out = lat_o + ((size_t)item * p.rows + row) * D_L;
+  T* o_out = lat_o + ((size_t)item * p.rows + row) * D_L;
   float* l_out = lat_lse + (size_t)item * p.rows + row;
   if (item < p.ap_chunks) {
     const int t0 = min(p.Ls, item * p.ap_chunk), t1 = min(p.Ls, t0 + p.ap_chunk);
-    attend_range<D_ROW, D_L>(
+    attend_range<D_ROW, D_L, T>(
         q_lds, t0, t1, scale,
         [=](int t, int i) {
           return i < D_L ? to_float(pc[(size_t)t * D_L + i]) : to_float(pr[(size_t)t * D_R + i - D_L]);
@@ -236,7 +236,7 @@ simple_absorb_kernel(Plan p, const T* __restrict__ qabs, const T* __restrict__ p
     auto rowp = [=](int j) {
       return pool + ((size_t)bt[j / block_size] * block_size + j % block_size) * D_ROW;
     };
-    attend_range<D_ROW, D_L>(
+    attend_range<D_ROW, D_L, T>(
         q_lds, t0, t1, scale, [=](int j, int i) { return to_float(rowp(j)[i]); },
         [=](int j, int d) { return to_float(rowp(j)[d]); }, o_out, l_out);
   }
@@ -248,7 +248,7 @@ simple_absorb_kernel(Plan p, const T* __restrict__ qabs, const T* __restrict__ p
 template <typename T>
 __global__ void __launch_bounds__(NT)
 simple_finalize_kernel(Plan p, const float* __restrict__ naive_o,
-                       const float* __restrict__ naive_lse, const float* __restrict__ lat_o,
+                       const float* __restrict__ naive_lse, const T* __restrict__ lat_o,
                        const float* __restrict__ lat_lse, const T* __restrict__ w_uv,
                        T* __restrict__ out, float* __restrict__ lse_out) {
   __shared__ float lat[D_L];
@@ -266,8 +266,8 @@ simple_finalize_kernel(Plan p, const float* __restrict__ naive_o,
         if (li == -INFINITY) continue;
         const float w = expf(li - m);
         z += w;
-        const float* src = lat_o + ((size_t)i * p.rows + row) * D_L;
-        for (int c = 0; c < D_L / NT; c++) acc[c] += w * src[tid + c * NT];
+        const T* src = lat_o + ((size_t)i * p.rows + row) * D_L;
+        for (int c = 0; c < D_L / NT; c++) acc[c] += w * to_float(src[tid + c * NT]);
       }
       const float inv = 1.f / z;
       // the latent output passes through the I/O dtype before the up-projection, as it does
@@ -325,14 +325,14 @@ void simple_stage_absorb(const Plan& p, const DecodeArgs& a) {
                      a.stream, p, (const T*)(a.ws + p.off_qabs), (const T*)a.prefix_ckv,
                      (const T*)a.prefix_krope, (const T*)a.suffix_pool, a.block_table,
                      a.suffix_lens, a.max_blocks, a.block_size, a.sm_scale,
-                     (float*)(a.ws + p.off_lat_o), (float*)(a.ws + p.off_lat_lse));
+                     (T*)(a.ws + p.off_lat_o), (float*)(a.ws + p.off_lat_lse));
 }
 template <typename T>
 void simple_stage_finalize(const Plan& p, const DecodeArgs& a) {
   if (p.rows == 0) return;
   hipLaunchKernelGGL(simple_finalize_kernel<T>, dim3((unsigned)p.rows), dim3(NT), 0, a.stream, p,
                      (const float*)(a.ws + p.off_naive_o), (const float*)(a.ws + p.off_naive_lse),
-                     (const float*)(a.ws + p.off_lat_o), (const float*)(a.ws + p.off_lat_lse),
+                     (const T*)(a.ws + p.off_lat_o), (const float*)(a.ws + p.off_lat_lse),
                      (const T*)a.w_uv, (T*)a.out, a.lse_out);
 }
 #define TMLA_INSTANTIATE(T)                                                        \
