@@ -57,6 +57,21 @@ __device__ inline short4v lds_read_tr16_b64(uint32_t addr) {
   return v;
 }
 
+// LDS writes and a float4 read for small exchange buffers next to the streamed tiles (same
+// reason for assembly: a compiler-visible LDS access would wait for every transfer in flight)
+__device__ inline void lds_write_b32(uint32_t addr, float v) {
+  asm volatile("ds_write_b32 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+template <int OFF>
+__device__ inline void lds_write_b128(uint32_t addr, bf16x8 v) {
+  asm volatile("ds_write_b128 %0, %1 offset:%2" ::"v"(addr), "v"(v), "n"(OFF) : "memory");
+}
+__device__ inline f32x4 lds_read_f32x4(uint32_t addr) {
+  f32x4 v;
+  asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+  return v;
+}
+
 template <int N>
 __device__ inline void vm_wait() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
