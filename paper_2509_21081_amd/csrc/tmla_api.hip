@@ -70,7 +70,7 @@ int make_plan(const tmla_dims* dims, int mode, int B, int Sq, int Ls, int max_su
     // absorb pass: one workgroup owns a request, one token chunk and up to 64 of its S_q*H query
     // rows (with at most 16 rows: four consecutive chunks, one per wavefront).  Chunks are kept
     // as long as the grid still covers the chip about twice: every extra chunk costs a
-    // 512-wide fp32 partial per row and a workgroup start-up.
+    // 512-wide partial per row and a workgroup start-up.
     const int R = Sq * H;
     const int per_wg = R <= 16 ? 4 : 1;
     const int wgs = std::max(1, B * ceil_div(R, 64));

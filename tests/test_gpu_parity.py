@@ -38,6 +38,16 @@ SMALL_CASES = {
                           seed=31),
     "wide_batch": dict(batch=70, heads=16, q_len=1, prefix_len=130, suffix_min=0, suffix_max=70,
                        seed=27),
+    # 48 query rows per request: the second 32-row query block of a workgroup is half empty
+    "h48_half_block": dict(batch=3, heads=48, q_len=1, prefix_len=90, suffix_min=30,
+                           suffix_max=200, seed=32),
+    # 96 rows: the second workgroup of a request holds one full and one empty query block;
+    # q_len = 2 puts the causal edge inside a 64-token step
+    "h48_mtp_empty_block": dict(batch=3, heads=48, q_len=2, prefix_len=65, suffix_min=60,
+                                suffix_max=135, seed=33),
+    # suffix lengths straddling the 32/64-token tile and step boundaries, causal over 3 queries
+    "h32_step_edges": dict(batch=9, heads=32, q_len=3, prefix_len=64, suffix_min=61,
+                           suffix_max=69, seed=34),
 }
 
 _cache = {}
@@ -63,6 +73,21 @@ def test_small_cases(case, dtype, mode, flags, gpu_device):
     print(f"case={case} dtype={dtype} mode={mode} flags={flags}", flush=True)
     got, got_lse = Hh.run_library(wl, mode, gpu_device, flags=flags)
     Hh.assert_parity(got, got_lse, ref, ref_lse, dtype, f"{case}/{dtype}/{mode}",
+                     logit_gain=wl.spec.q_gain)
+
+
+@pytest.mark.parametrize("mode", ["mixed", "absorb_only"])
+@pytest.mark.parametrize("case", ["h128_many_tiles", "mtp_h32", "h48_mtp_empty_block",
+                                  "ragged_h16"])
+def test_forced_small_chunks(case, mode, gpu_device, monkeypatch):
+    """Token chunks of one 64-token step (32 tokens for the <= 16-row kernel's wavefront shares):
+    every chunk boundary, empty chunks of short requests and the merge of many latent partials."""
+    monkeypatch.setenv("TMLA_SUFFIX_CHUNK", "64")
+    monkeypatch.setenv("TMLA_ABSORB_PREFIX_CHUNK", "64")
+    wl, (ref, ref_lse) = _workload_and_ref(case, "bf16")
+    print(f"forced chunks case={case} mode={mode}", flush=True)
+    got, got_lse = Hh.run_library(wl, mode, gpu_device)
+    Hh.assert_parity(got, got_lse, ref, ref_lse, "bf16", f"{case}/chunk64/{mode}",
                      logit_gain=wl.spec.q_gain)
 
 
