@@ -279,16 +279,23 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
       alpha[q] = m[q] - m_use[q];   // exponent of the rescale factor (m = -inf -> factor 0)
       m[q] = m_new;
     }
-    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+    // (in step 0 every accumulator is still zero: nothing to rescale)
+    if (step > 0 && __builtin_amdgcn_ballot_w64(grow) != 0) {
       alpha[0] = fast_exp2(alpha[0]);
       alpha[1] = fast_exp2(alpha[1]);
       l *= alpha[qb];
 #pragma unroll
       for (int mb = 0; mb < 4; mb++)
 #pragma unroll
-        for (int q = 0; q < 2; q++)
+        for (int q = 0; q < 2; q++) {
+          // the accumulators live in accumulation registers, which the vector ALU cannot address;
+          // routing them through this statement keeps their copies inside the rare branch
+          // (otherwise the copies out are hoisted and run in every step)
+          asm volatile("" : "+a"(o[mb][q]));
 #pragma unroll
           for (int v = 0; v < 16; v++) o[mb][q][v] *= alpha[q];
+          asm volatile("" : "+a"(o[mb][q]));
+        }
     }
     {
       const float mu = m_use[qb];
