@@ -254,10 +254,16 @@ __global__ void __launch_bounds__(256, 1) absorb16_kernel(Absorb16Args a) {
     if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {
       const float alpha = fast_exp2(m - m_use);
       l *= alpha;
+      // the accumulators live in accumulation registers, which the vector ALU cannot address;
+      // routing them through these statements keeps their copies inside the rare branch
+      // (otherwise the copies are hoisted and run for every tile)
 #pragma unroll
-      for (int mb = 0; mb < 32; mb++)
+      for (int mb = 0; mb < 32; mb++) {
+        asm volatile("" : "+a"(o[mb]));
 #pragma unroll
         for (int v = 0; v < 4; v++) o[mb][v] *= alpha;
+        asm volatile("" : "+a"(o[mb]));
+      }
     }
     m = m_new;
     bf16x8 p;

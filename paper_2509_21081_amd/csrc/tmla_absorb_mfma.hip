@@ -240,10 +240,14 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
     bool rescale;
     const float alpha = softmax_block(sacc, m, l, a.c, limit, g, p[0], p[1], rescale);
     if (rescale) {
+      // (the asm statements keep the accumulator <-> vector register copies inside this branch)
 #pragma unroll
-      for (int mb = 0; mb < MBW; mb++)
+      for (int mb = 0; mb < MBW; mb++) {
+        asm volatile("" : "+a"(o[mb]));
 #pragma unroll
         for (int v = 0; v < 16; v++) o[mb][v] *= alpha;
+        asm volatile("" : "+a"(o[mb]));
+      }
     }
     {
       // step st = 2*mb + kk; groups of 4 steps (8 transposing reads), double buffered

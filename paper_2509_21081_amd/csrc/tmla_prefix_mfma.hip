@@ -368,9 +368,15 @@ __device__ inline void ts_block(uint32_t blk, int lane, const bf16x8 (&qf)[2][12
         softmax_block(sacc[nb], m[nb], l[nb], c, limit, g, p[nb][0], p[nb][1], rescale);
     if (rescale) {
 #pragma unroll
-      for (int db = 0; db < 4; db++)
+      for (int db = 0; db < 4; db++) {
+        // the accumulators live in accumulation registers, which the vector ALU cannot address;
+        // routing them through these statements keeps their copies inside the rare branch
+        // (otherwise the copies out are hoisted and run for every block)
+        asm volatile("" : "+a"(o[db][nb]));
 #pragma unroll
         for (int v = 0; v < 16; v++) o[db][nb][v] *= alpha;
+        asm volatile("" : "+a"(o[db][nb]));
+      }
     }
   }
   lgkm_wait<0>(vf[0], vf[1], vf[2], vf[3]);
