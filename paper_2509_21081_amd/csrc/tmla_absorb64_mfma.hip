@@ -98,30 +98,33 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
   dl.off1 = (lane ^ 1) << 4;
   dl.rope_row = 8 * wave + (lane >> 3);
   dl.rope_ch = ((lane & 7) ^ ((lane >> 3) & 7)) << 4;
-  // tile = 32 tokens starting at t0 + 32 * tile; a tile past the end of the chunk (second half of
-  // the last step) is filled with the chunk's last row: all its scores are masked
-  auto tile_src = [&](int tile) __attribute__((always_inline)) {
-    RowSrc s;
-    int tok0 = t0 + tile * 32;
-    s.last = t1 - 1 - tok0;
-    if (s.last < 0) {
-      tok0 = t1 - 1;
-      s.last = 0;
-    }
+  // The two tiles (32 tokens each) of step `step`, tokens t0 + 64 * step ...  Suffix chunks start
+  // on a 64-token boundary and cache blocks hold a multiple of 64 tokens, so one block-table
+  // entry serves a step.  A second tile past the end of the chunk is filled with the chunk's
+  // last row: all its scores are masked.
+  const int bs_shift = __builtin_ctz((unsigned)a.block_size);
+  auto step_src = [&](int step, RowSrc& s0, RowSrc& s1) __attribute__((always_inline)) {
+    const int tok0 = t0 + step * 64;
+    s0.last = t1 - 1 - tok0;              // >= 0 for every step of the chunk
     if (is_prefix) {
-      s.lat = (const char*)a.pc + (size_t)tok0 * (D_L * 2);
-      s.rope = (const char*)a.pr + (size_t)tok0 * (D_R * 2);
-      s.lat_stride = D_L * 2;
-      s.rope_stride = D_R * 2;
+      s0.lat = (const char*)a.pc + (size_t)tok0 * (D_L * 2);
+      s0.rope = (const char*)a.pr + (size_t)tok0 * (D_R * 2);
+      s0.lat_stride = D_L * 2;
+      s0.rope_stride = D_R * 2;
     } else {
-      const int bi = __builtin_amdgcn_readfirstlane(tok0 / a.block_size - first_blk);
+      const int bi = __builtin_amdgcn_readfirstlane((tok0 >> bs_shift) - first_blk);
       const int blk = bi < 64 ? __builtin_amdgcn_readlane(bt_cache, bi)
                               : scalar_load_i32(bt + first_blk + bi);
-      s.lat = (const char*)(a.pool + ((size_t)blk * a.block_size + tok0 % a.block_size) * D_ROW);
-      s.rope = s.lat + D_L * 2;
-      s.lat_stride = s.rope_stride = D_ROW * 2;
+      s0.lat = (const char*)(a.pool +
+                             (((size_t)blk << bs_shift) + (tok0 & (a.block_size - 1))) * D_ROW);
+      s0.rope = s0.lat + D_L * 2;
+      s0.lat_stride = s0.rope_stride = D_ROW * 2;
     }
-    return s;
+    s1 = s0;
+    const int adv = s0.last >= 32 ? 32 : s0.last;   // rows to the second tile (or to the last row)
+    s1.lat += (size_t)adv * s0.lat_stride;
+    s1.rope += (size_t)adv * s0.rope_stride;
+    s1.last = s0.last >= 32 ? s0.last - 32 : 0;
   };
 
   // per-lane LDS byte offsets inside a tile (layout in tmla_absorb_tile.hpp)
@@ -161,8 +164,12 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
       issue_all(qs, smem + (2 + j) * AB_TILE_BYTES, dl);
     }
   }
-  issue_all(tile_src(0), smem, dl);
-  issue_all(tile_src(1), smem + AB_TILE_BYTES, dl);
+  {
+    RowSrc s0, s1;
+    step_src(0, s0, s1);
+    issue_all(s0, smem, dl);
+    issue_all(s1, smem + AB_TILE_BYTES, dl);
+  }
   vm_wait<2 * AB_DMA_PER_WAVE>();
   raw_barrier();
   bf16x8 qf[36];
@@ -195,10 +202,7 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
     raw_barrier();   // A
     const bool do_pf = step + 1 < nstep;
     RowSrc pf0, pf1;
-    if (do_pf) {
-      pf0 = tile_src(2 * step + 2);
-      pf1 = tile_src(2 * step + 3);
-    }
+    if (do_pf) step_src(step + 1, pf0, pf1);
     char* pf_dst = smem + (((step + 1) & 1) * 2) * AB_TILE_BYTES;
     const uint32_t sbase = smem_base + ((step & 1) * 2) * AB_TILE_BYTES;   // the step's two tiles
 
@@ -241,9 +245,24 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
         static_for<4>([&](auto j) {
           sacc = mfma32(f[cur][j], qf[4 * G + decltype(j)::value], sacc);
         });
-        if (do_pf) {   // two of the next step's 18 transfers per group
-          issue_part<G>(pf0, pf_dst, dl);
-          issue_part<G>(pf1, pf_dst + AB_TILE_BYTES, dl);
+        // The next step's transfers.  A transfer holds up the issuing wavefront while the
+        // memory pipeline takes it, and longer when other wavefronts present theirs at the same
+        // time, so the wavefronts take turns: wavefront w issues in groups w and w + 4 (a whole
+        // tile each), wavefront 0, which has three groups (0, 4, 8), a third of its 18 in each.
+        if (do_pf) {
+          if constexpr (G == 0 || G == 4 || G == 8) {
+            if (wave == 0) {
+              static_for<6>([&](auto i_) {
+                constexpr int k = (G / 4) * 6 + decltype(i_)::value;   // 0 .. 17
+                if constexpr (k < 9) issue_part<k>(pf0, pf_dst, dl);
+                else issue_part<k - 9>(pf1, pf_dst + AB_TILE_BYTES, dl);
+              });
+            }
+          } else if constexpr (G < 4) {
+            if (wave == G) issue_all(pf0, pf_dst, dl);
+          } else {
+            if (wave == G - 4) issue_all(pf1, pf_dst + AB_TILE_BYTES, dl);
+          }
         }
       });
     }
