@@ -336,7 +336,23 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
       lds_write_b128<0>(p_wr, p0);
       lds_write_b128<1024>(p_wr, p1);
     }
-    lgkm_wait<0>();
+    // the first group of transposed cache fragments does not depend on the probabilities: it is
+    // requested before barrier C (the probability writes were issued earlier and complete first)
+    const uint32_t va = sbase + v_off;
+    short4v lo[2][4], hi[2][4];
+    auto rdv = [&](auto grp_, auto buf_) __attribute__((always_inline)) {
+      constexpr int G = decltype(grp_)::value;   // = mb
+      constexpr int D = decltype(buf_)::value;
+      static_for<4>([&](auto ks_) {
+        constexpr int ks = decltype(ks_)::value;
+        constexpr int thp = ks >> 1, kk = ks & 1;
+        constexpr int off = thp * AB_TILE_BYTES + (16 * kk) * AB_ROW_BYTES + 64 * G;
+        lo[D][ks] = lds_read_tr16_b64<off>(va);
+        hi[D][ks] = lds_read_tr16_b64<off + 8 * AB_ROW_BYTES>(va);
+      });
+    };
+    rdv(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    lgkm_wait<8>();
     raw_barrier();   // C
 
     // ---- outputs: own latent quarter, all 64 tokens, both query blocks
@@ -349,26 +365,11 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
         pf[ks][0] = lds_read_b128<(0 + 2 * thp) * 2048 + kk * 1024>(p_rd);
         pf[ks][1] = lds_read_b128<(1 + 2 * thp) * 2048 + kk * 1024>(p_rd);
       });
-      // transposed cache fragments: unit u = 4 * mb + ks, groups of 4 units (8 reads), double
+      // transposed cache fragments: one group per latent block mb (4 k-steps, 8 reads), double
       // buffered; each fragment feeds the MFMAs of both query blocks
-      const uint32_t va = sbase + v_off;
-      short4v lo[2][4], hi[2][4];
-      auto rdv = [&](auto grp_, auto buf_) __attribute__((always_inline)) {
-        constexpr int G = decltype(grp_)::value;   // = mb
-        constexpr int D = decltype(buf_)::value;
-        static_for<4>([&](auto ks_) {
-          constexpr int ks = decltype(ks_)::value;
-          constexpr int thp = ks >> 1, kk = ks & 1;
-          constexpr int off = thp * AB_TILE_BYTES + (16 * kk) * AB_ROW_BYTES + 64 * G;
-          lo[D][ks] = lds_read_tr16_b64<off>(va);
-          hi[D][ks] = lds_read_tr16_b64<off + 8 * AB_ROW_BYTES>(va);
-        });
-      };
-      rdv(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
       static_for<4>([&](auto ks_) {
         constexpr int ks = decltype(ks_)::value;
-        // the probability fragments were requested before the first transposed group
-        lgkm_wait<8>(pf[ks][0], pf[ks][1]);
+        lgkm_wait<0>(pf[ks][0], pf[ks][1]);
       });
       static_for<4>([&](auto mb_) {
         constexpr int mb = decltype(mb_)::value;
