@@ -20,7 +20,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
-constexpr float RESCALE_TAU = 8.f;
+constexpr float RESCALE_TAU = 8.f;   // softmax_block_fast assumes 2^(RESCALE_TAU + 4) = 4096
 
 __device__ inline f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -100,6 +100,42 @@ __device__ inline float softmax_block(f32x16& s, float& m, float& l, float c, in
   }
   l += sum;
   return alpha;
+}
+
+// Same contract as softmax_block, for blocks known to be full (no masking), with a shortcut for
+// the common case that the exponent reference is still good: the probabilities are formed
+// against the current reference straight away, and their per-lane sum -- taken by the bf16 dot
+// instruction from the packed values the second product will use -- doubles as the range check:
+// no probability can exceed a sum that stays below 2^(RESCALE_TAU + 4).  Then neither the block
+// maximum nor the exchange between the lane halves is needed.  Otherwise (first block, or a
+// score far above the reference) the scores are still intact and the full update runs.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ inline float softmax_block_fast(f32x16& s, float& m, float& l, float c, int g,
+                                           bf16x8& p0, bf16x8& p1, bool& rescale) {
+  bf16x8 q0, q1;
+#pragma unroll
+  for (int v = 0; v < 8; v++) {
+    q0[v] = (__bf16)fast_exp2(__builtin_fmaf(s[v], c, -m));       // m = -inf gives inf: falls through
+    q1[v] = (__bf16)fast_exp2(__builtin_fmaf(s[8 + v], c, -m));
+  }
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  float sum = 0.f;
+#pragma unroll
+  for (int v = 0; v < 8; v += 2) {
+    const bf16x2 a = {q0[v], q0[v + 1]};
+    const bf16x2 b = {q1[v], q1[v + 1]};
+    sum = __builtin_amdgcn_fdot2_f32_bf16(a, ones, sum, false);
+    sum = __builtin_amdgcn_fdot2_f32_bf16(b, ones, sum, false);
+  }
+  const bool good = sum <= 16.f * 256.f;   // 2^(RESCALE_TAU + 4); false for inf and NaN
+  if (__builtin_amdgcn_ballot_w64(!good) == 0) {
+    l += sum;
+    p0 = q0;
+    p1 = q1;
+    rescale = false;
+    return 1.f;
+  }
+  return softmax_block<false>(s, m, l, c, 32, g, p0, p1, rescale);
 }
 
 }  // namespace tmla

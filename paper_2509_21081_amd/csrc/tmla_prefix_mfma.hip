@@ -222,9 +222,13 @@ __global__ void __launch_bounds__(512 / NB, 1) prefix_attn_query_split_kernel(Pr
   auto softmax_all = [&](f32x16 (&s)[NB], bf16x8 (&p)[NB][2], auto mask_tag, int limit)
                          __attribute__((always_inline)) {
 #pragma unroll
-    for (int nb = 0; nb < NB; nb++)
-      alpha[nb] = softmax_block<decltype(mask_tag)::value>(s[nb], m[nb], l[nb], a.c, limit, g,
-                                                           p[nb][0], p[nb][1], resc[nb]);
+    for (int nb = 0; nb < NB; nb++) {
+      if constexpr (decltype(mask_tag)::value)
+        alpha[nb] = softmax_block<true>(s[nb], m[nb], l[nb], a.c, limit, g, p[nb][0], p[nb][1],
+                                        resc[nb]);
+      else
+        alpha[nb] = softmax_block_fast(s[nb], m[nb], l[nb], a.c, g, p[nb][0], p[nb][1], resc[nb]);
+    }
   };
   auto rescale_o = [&]() __attribute__((always_inline)) {
 #pragma unroll
