@@ -104,8 +104,9 @@ int typhoon_mla_expand_pool(const tmla_dims* dims, int32_t num_blocks, int32_t b
 /*
  * Break-even batch size B_theta of Section 3.2, (D_qk + D_v) / (q_len (2 D_l + D_r)) * T / M, with
  * the throughput T of this library's absorb kernel over a shared prefix and the bandwidth M of its
- * naive prefix kernel as measured on MI355X (about 300 TFLOP/s and 5 TB/s, giving 17.6 / q_len; the
- * measured cross-over at prefix 4096 / suffix 512 lies between batch 4 and 16).  The environment
+ * naive prefix kernel as measured on MI355X at the small batches where the two meet (about
+ * 100 TFLOP/s and 5 TB/s, giving 5.9 / q_len; the measured cross-over at prefix 4096 /
+ * suffix 512 lies between batch 4 and 8).  The environment
  * variable TMLA_AUTO_BATCH_THRESHOLD overrides it.  TMLA_MODE_AUTO uses mixed when
  * batch >= this value.
  */

@@ -78,7 +78,7 @@ def suffix_kernel_work(sh, n_partials_rows=0):
     n_partials_rows = number of (row, chunk) partials actually written."""
     rows = sh.B * sh.S_q * sh.H
     bytes_ = (sh.sum_L_n * (D_L + D_R) * sh.elem_bytes + rows * (D_L + D_R) * sh.elem_bytes
-              + n_partials_rows * (D_L + 1) * 4)
+              + n_partials_rows * (D_L * sh.elem_bytes + 4))
     flops = 2 * sh.S_q * sh.sum_L_n * sh.H * (2 * D_L + D_R)
     return dict(bytes=bytes_, flops=flops)
 

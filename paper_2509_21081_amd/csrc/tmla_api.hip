@@ -204,8 +204,11 @@ static int check_decode_sizes(const tmla_dims* dims, int mode, int batch, int q_
   return TMLA_OK;
 }
 
-// measured on MI355X: absorb attention over a shared prefix ~300 TFLOP/s, naive prefix ~5 TB/s
-static constexpr double AUTO_T_FLOPS = 300e12, AUTO_M_BYTES = 5e12;
+// Measured on MI355X near the cross-over: absorb attention over a shared prefix delivers
+// ~100 TFLOP/s at the small batches in question (it reaches ~450 only with hundreds of query rows
+// per request), the naive prefix pass streams at ~5 TB/s.  The measured cross-over at
+// L_s = 4096, H = 128 lies between batch 4 and 8.
+static constexpr double AUTO_T_FLOPS = 100e12, AUTO_M_BYTES = 5e12;
 
 double typhoon_mla_auto_batch_threshold(int32_t q_len) {
   const char* e = getenv("TMLA_AUTO_BATCH_THRESHOLD");
