@@ -182,3 +182,53 @@ def test_auto_mode_matches_oracle(case, gpu_device):
     print(f"auto mode case={case}", flush=True)
     got, got_lse = Hh.run_library(wl, "auto", gpu_device)
     Hh.assert_parity(got, got_lse, ref, ref_lse, "bf16", f"{case}/auto")
+
+
+@pytest.mark.parametrize("case", ["h128_many_tiles", "ragged_h16"])
+def test_decode_replays_from_a_hip_graph(case, gpu_device):
+    """The library only enqueues kernels on the caller's stream (no allocation, no host
+    synchronisation, no memset nodes), so a decode step can be captured into a HIP graph.  Every
+    replay, with eager work and synchronisations in between, must reproduce the eager result bit
+    for bit, also after the inputs have changed in place."""
+    wl, (ref, ref_lse) = _workload_and_ref(case, "bf16")
+    d = wl.to(gpu_device)
+    dims = Hh.dims_of(wl)
+    L_s = wl.spec.prefix_len
+    pk, pv = T.typhoon_mla_expand_prefix(dims, d.prefix_ckv, d.prefix_krope, d.w_uk, d.w_uv)
+    B, S, H = wl.spec.batch, wl.spec.q_len, wl.spec.heads
+    out = torch.empty((B, S, H, 128), dtype=torch.bfloat16, device=gpu_device)
+    lse = torch.empty((B, S, H), dtype=torch.float32, device=gpu_device)
+    nbytes = T.typhoon_mla_decode_workspace_bytes(dims, T.MODE_MIXED, B, S, L_s, wl.max_suffix_len)
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=gpu_device)
+    q = d.q.clone()
+
+    def step():
+        T.typhoon_mla_decode(dims, "mixed", q, L_s, prefix_k=pk, prefix_v=pv,
+                             suffix_pool=d.pool, block_table=d.block_table,
+                             suffix_lens=d.suffix_lens, max_suffix_len=wl.max_suffix_len,
+                             w_uk=d.w_uk, w_uv=d.w_uv, out=out, lse_out=lse, workspace=ws)
+
+    print(f"graph capture case={case}", flush=True)
+    step()                                   # eager: also performs the one-time kernel set-up
+    torch.cuda.synchronize(gpu_device)
+    eager = (out.clone(), lse.clone())
+    Hh.assert_parity(out.double().cpu().numpy(), lse.double().cpu().numpy(), ref, ref_lse, "bf16",
+                     f"{case}/eager")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        out.fill_(float("nan"))              # eager work between replays
+        lse.fill_(float("nan"))
+        torch.cuda.synchronize(gpu_device)
+        graph.replay()
+        torch.cuda.synchronize(gpu_device)
+        assert torch.equal(out, eager[0]) and torch.equal(lse, eager[1]), f"replay {rep} differs"
+    # new queries written in place are picked up by the next replay
+    q.copy_(torch.flip(d.q, dims=[0]))
+    graph.replay()
+    torch.cuda.synchronize(gpu_device)
+    flipped = (out.clone(), lse.clone())
+    step()
+    torch.cuda.synchronize(gpu_device)
+    assert torch.equal(out, flipped[0]) and torch.equal(lse, flipped[1])
