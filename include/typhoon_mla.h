@@ -150,6 +150,50 @@ int typhoon_mla_decode(const tmla_dims* dims, int32_t mode, int32_t batch, int32
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Multi-level (tree-shaped) shared prefixes.  Section 3.1 ("Prefill") speaks of a tree-like query
+ * structure formed from the requests and their shared prefix, and the related-work discussion of
+ * prefix sharing says that the handling of tree-structured caches applies to the naive and the
+ * absorb part alike.  Here a request's context is the concatenation of the nodes on its path (e.g. a system prompt shared by all requests, then a per-tenant prompt shared by a
+ * group) followed by its own suffix.  Each node is attended in the naive formulation over its
+ * own expanded K/V (typhoon_mla_expand_prefix per node) by exactly the requests that share it,
+ * the suffixes in the absorb formulation, and all partials are merged with CombineLSE -- the
+ * merge of Algorithm 1 step 8 with one more partial per level.
+ *
+ * A node covers the contiguous request range [batch_begin, batch_begin + batch_count) and sits on
+ * `level` (0 = root side).  Nodes of one level must not overlap; a request may skip a level.
+ * The array of nodes lives in HOST memory and is only read during the call; k/v are device
+ * pointers in the expanded layout for `len` tokens.  Attention is over a set, so the order of the
+ * levels has no effect on the result.
+ */
+typedef struct {
+  const void* k;        /* expanded K of the node's tokens (device) */
+  const void* v;        /* expanded V (device)                      */
+  int32_t len;          /* tokens in the node, >= 0                 */
+  int32_t level;        /* 0 <= level < 8                           */
+  int32_t batch_begin;  /* first request sharing the node           */
+  int32_t batch_count;  /* number of requests sharing it, >= 0      */
+} tmla_prefix_node;
+
+/* Scratch bytes typhoon_mla_decode_tree needs (a pure host function; 0 on invalid arguments). */
+size_t typhoon_mla_decode_tree_workspace_bytes(const tmla_dims* dims, int32_t batch, int32_t q_len,
+                                               const tmla_prefix_node* nodes, int32_t num_nodes,
+                                               int32_t max_suffix_len);
+
+/*
+ * One decode step over tree-shaped shared prefixes (mixed formulation).  Arguments as for
+ * typhoon_mla_decode, with `nodes` in place of the single prefix; num_nodes == 0 is the
+ * suffix-only case.  Errors: TMLA_ERR_INVALID_ARG also for a node range outside the batch, a
+ * level outside [0, 8) or two overlapping nodes of one level.
+ */
+int typhoon_mla_decode_tree(const tmla_dims* dims, int32_t batch, int32_t q_len, const void* q,
+                            const tmla_prefix_node* nodes, int32_t num_nodes,
+                            const void* suffix_pool, int32_t num_blocks, int32_t block_size,
+                            const int32_t* block_table, int32_t max_blocks,
+                            const int32_t* suffix_lens, int32_t max_suffix_len, const void* w_uk,
+                            const void* w_uv, void* out, float* lse_out, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+/*
  * CombineLSE alone (Algorithm 1 step 8; Section 3.2): exact merge of `num_partials` normalised
  * partial outputs with their natural-log LSEs.
  *   partial_out in [num_partials, rows, width] fp32,  partial_lse in [num_partials, rows] fp32

@@ -24,7 +24,8 @@ EXPORTS = [
     "typhoon_mla_status_string", "typhoon_mla_expanded_k_bytes", "typhoon_mla_expanded_v_bytes",
     "typhoon_mla_expand_prefix", "typhoon_mla_expand_pool", "typhoon_mla_decode_workspace_bytes",
     "typhoon_mla_decode", "typhoon_mla_combine_lse", "typhoon_mla_set_debug_flags",
-    "typhoon_mla_auto_batch_threshold",
+    "typhoon_mla_auto_batch_threshold", "typhoon_mla_decode_tree_workspace_bytes",
+    "typhoon_mla_decode_tree",
 ]
 
 
@@ -32,6 +33,11 @@ class tmla_dims(Structure):
     _fields_ = [("num_heads", c_int32), ("kv_lora_rank", c_int32), ("qk_nope_dim", c_int32),
                 ("qk_rope_dim", c_int32), ("v_head_dim", c_int32), ("sm_scale", c_float),
                 ("dtype", c_int32)]
+
+
+class tmla_prefix_node(Structure):
+    _fields_ = [("k", c_void_p), ("v", c_void_p), ("len", c_int32), ("level", c_int32),
+                ("batch_begin", c_int32), ("batch_count", c_int32)]
 
 
 def make_dims(num_heads, sm_scale, dtype, kv_lora_rank=512, qk_nope_dim=128, qk_rope_dim=64,
@@ -77,6 +83,15 @@ def lib():
                                               c_void_p, c_int32, c_void_p, c_void_p]
         L.typhoon_mla_auto_batch_threshold.restype = ctypes.c_double
         L.typhoon_mla_auto_batch_threshold.argtypes = [c_int32]
+        N = POINTER(tmla_prefix_node)
+        L.typhoon_mla_decode_tree_workspace_bytes.restype = c_size_t
+        L.typhoon_mla_decode_tree_workspace_bytes.argtypes = [P, c_int32, c_int32, N, c_int32,
+                                                              c_int32]
+        L.typhoon_mla_decode_tree.restype = c_int
+        L.typhoon_mla_decode_tree.argtypes = (
+            [P, c_int32, c_int32, c_void_p, N, c_int32, c_void_p, c_int32, c_int32, c_void_p,
+             c_int32, c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+             c_size_t, c_void_p])
         L.typhoon_mla_set_debug_flags.restype = c_int
         L.typhoon_mla_set_debug_flags.argtypes = [c_int]
         _lib = L
@@ -205,3 +220,45 @@ def typhoon_mla_combine_lse(partial_out, partial_lse, out_dtype=torch.float32, w
                                        _ptr(out), code, _ptr(lse), _stream(dev))
     _check(st, "typhoon_mla_combine_lse")
     return out, lse
+
+
+def make_nodes(nodes):
+    """nodes: iterable of (prefix_k, prefix_v, len, level, batch_begin, batch_count) with the
+    expanded tensors of typhoon_mla_expand_prefix.  Returns a ctypes array (host memory)."""
+    arr = (tmla_prefix_node * max(1, len(nodes)))()
+    for i, (k, v, ln, level, b0, bc) in enumerate(nodes):
+        arr[i] = tmla_prefix_node(k.data_ptr() if k is not None else None,
+                                  v.data_ptr() if v is not None else None, ln, level, b0, bc)
+    return arr
+
+
+def typhoon_mla_decode_tree_workspace_bytes(dims, batch, q_len, nodes, max_suffix_len):
+    arr = make_nodes(nodes)
+    return lib().typhoon_mla_decode_tree_workspace_bytes(ctypes.byref(dims), batch, q_len, arr,
+                                                         len(nodes), max_suffix_len)
+
+
+def typhoon_mla_decode_tree(dims, q, nodes, suffix_pool=None, block_table=None, suffix_lens=None,
+                            max_suffix_len=0, w_uk=None, w_uv=None, out=None, lse_out=None,
+                            workspace=None, want_lse=True):
+    """One decode step over tree-shaped shared prefixes; returns (out, lse)."""
+    B, S_q, H, _ = q.shape
+    dev = q.device
+    arr = make_nodes(nodes)
+    if out is None:
+        out = torch.empty((B, S_q, H, 128), dtype=q.dtype, device=dev)
+    if lse_out is None and want_lse:
+        lse_out = torch.empty((B, S_q, H), dtype=torch.float32, device=dev)
+    if workspace is None:
+        nbytes = lib().typhoon_mla_decode_tree_workspace_bytes(ctypes.byref(dims), B, S_q, arr,
+                                                               len(nodes), max_suffix_len)
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    num_blocks = suffix_pool.shape[0] if suffix_pool is not None else 0
+    block_size = suffix_pool.shape[1] if suffix_pool is not None else 64
+    max_blocks = block_table.shape[1] if block_table is not None else 0
+    st = lib().typhoon_mla_decode_tree(
+        ctypes.byref(dims), B, S_q, _ptr(q), arr, len(nodes), _ptr(suffix_pool), num_blocks,
+        block_size, _ptr(block_table), max_blocks, _ptr(suffix_lens), max_suffix_len, _ptr(w_uk),
+        _ptr(w_uv), _ptr(out), _ptr(lse_out), _ptr(workspace), workspace.numel(), _stream(dev))
+    _check(st, "typhoon_mla_decode_tree")
+    return out, lse_out

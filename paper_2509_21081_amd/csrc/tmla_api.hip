@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <cstdlib>
 #include <cstring>
+#include <vector>
 
 #include "tmla_common.hpp"
 
@@ -36,6 +37,18 @@ static inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % 
 
 constexpr int NUM_CU = 256;  // MI355X compute units; work is cut to a small multiple of this
 
+// Token splits of a naive pass over Ls shared tokens for M queries per head.
+static void plan_prefix_splits(int H, int M, int Ls, int* p_chunk, int* np_split) {
+  const int wgs = std::max(1, H * (M > 128 ? ceil_div(M, 256) : ceil_div(M, 64)));
+  int splits = env_int("TMLA_PREFIX_SPLITS", 0);
+  if (splits <= 0) splits = std::max(1, NUM_CU / wgs);
+  splits = std::max(1, std::min(splits, ceil_div(Ls, 128)));
+  *p_chunk = round_up(ceil_div(Ls, splits), TOK_BLK);
+  *np_split = ceil_div(Ls, *p_chunk);
+}
+
+void layout_workspace(Plan* p);
+
 // Cuts the call into work items (token chunks) and lays the intermediates out in the workspace.
 // Chunk counts per request are bounds derived from host-visible sizes only; a chunk that turns
 // out empty on the device reports LSE = -inf and is skipped by the combine step.
@@ -53,12 +66,7 @@ int make_plan(const tmla_dims* dims, int mode, int B, int Sq, int Ls, int max_su
     // naive prefix pass: one workgroup owns a head and a block of up to 256 queries
     // (64 when the batch is small and the token-split kernel runs); one workgroup fits per
     // compute unit, so the prefix is split until the grid covers the chip once
-    const int wgs = std::max(1, H * (M > 128 ? ceil_div(M, 256) : ceil_div(M, 64)));
-    int splits = env_int("TMLA_PREFIX_SPLITS", 0);
-    if (splits <= 0) splits = std::max(1, NUM_CU / wgs);
-    splits = std::max(1, std::min(splits, ceil_div(Ls, 128)));
-    p->p_chunk = round_up(ceil_div(Ls, splits), TOK_BLK);
-    p->np_split = ceil_div(Ls, p->p_chunk);
+    plan_prefix_splits(H, M, Ls, &p->p_chunk, &p->np_split);
   }
   if (mode == TMLA_MODE_NAIVE_ONLY && max_suffix > 0) {
     int chunk = env_int("TMLA_NAIVE_SUFFIX_CHUNK", 0);
@@ -93,7 +101,12 @@ int make_plan(const tmla_dims* dims, int mode, int B, int Sq, int Ls, int max_su
   p->n_naive = p->np_split + p->ns_chunks;
   p->n_lat = p->ap_chunks + p->as_chunks;
 
-  const size_t esz = dims->dtype == TMLA_BF16 ? 2 : 4;
+  layout_workspace(p);
+  return TMLA_OK;
+}
+
+void layout_workspace(Plan* p) {
+  const size_t esz = p->dtype == TMLA_BF16 ? 2 : 4;
   size_t off = 0;
   p->off_qabs = off;      off = align_up(off + (p->n_lat ? (size_t)p->rows * D_ROW * esz : 0), 256);
   p->off_naive_o = off;   off = align_up(off + (size_t)p->n_naive * p->rows * D_V * 4, 256);
@@ -101,7 +114,6 @@ int make_plan(const tmla_dims* dims, int mode, int B, int Sq, int Ls, int max_su
   p->off_lat_o = off;     off = align_up(off + (size_t)p->n_lat * p->rows * D_L * esz, 256);
   p->off_lat_lse = off;   off = align_up(off + (size_t)p->n_lat * p->rows * 4, 256);
   p->total = off + 256;
-  return TMLA_OK;
 }
 
 static int64_t padded_tokens(const tmla_dims* dims, int64_t n) {
@@ -319,6 +331,146 @@ int typhoon_mla_decode(const tmla_dims* dims, int32_t mode, int32_t batch, int32
       if (g_debug_flags & 8) simple_stage_finalize<bf16_t>(p, a);
       else if ((st = mfma_finalize(p, a)) != TMLA_OK) return st;
     }
+  }
+  return hipGetLastError() == hipSuccess ? TMLA_OK : TMLA_ERR_HIP;
+}
+
+// ---- tree-shaped shared prefixes -----------------------------------------------------------
+constexpr int TREE_MAX_LEVELS = 8;
+
+struct TreePlan {
+  Plan p;                            // suffix plan + workspace layout; n_naive = all level slots
+  int level_slot0[TREE_MAX_LEVELS];  // first partial slot of a level
+  std::vector<int> chunk, splits;    // per node
+};
+
+// Validates the nodes and fixes the partial slots: a level owns as many slots as its most split
+// node; rows of a level that no node covers keep the LSE = -inf the slots are initialised with.
+static int make_tree_plan(const tmla_dims* dims, int batch, int q_len, const tmla_prefix_node* nodes,
+                          int num_nodes, int max_suffix_len, int block_size, TreePlan* tp) {
+  int st = check_decode_sizes(dims, TMLA_MODE_MIXED, batch, q_len, 0, max_suffix_len);
+  if (st != TMLA_OK) return st;
+  if (num_nodes < 0 || (num_nodes > 0 && !nodes)) return TMLA_ERR_INVALID_ARG;
+  make_plan(dims, TMLA_MODE_MIXED, batch, q_len, 0, max_suffix_len, block_size, &tp->p);
+  int level_slots[TREE_MAX_LEVELS] = {0};
+  tp->chunk.assign(num_nodes, 0);
+  tp->splits.assign(num_nodes, 0);
+  for (int i = 0; i < num_nodes; i++) {
+    const tmla_prefix_node& nd = nodes[i];
+    if (nd.len < 0 || nd.level < 0 || nd.level >= TREE_MAX_LEVELS || nd.batch_begin < 0 ||
+        nd.batch_count < 0 || (int64_t)nd.batch_begin + nd.batch_count > batch)
+      return TMLA_ERR_INVALID_ARG;
+    if (nd.len == 0 || nd.batch_count == 0) continue;
+    for (int j = 0; j < i; j++) {
+      const tmla_prefix_node& o = nodes[j];
+      if (o.level != nd.level || o.len == 0 || o.batch_count == 0) continue;
+      if (nd.batch_begin < o.batch_begin + o.batch_count && o.batch_begin < nd.batch_begin + nd.batch_count)
+        return TMLA_ERR_INVALID_ARG;
+    }
+    plan_prefix_splits(dims->num_heads, nd.batch_count * q_len, nd.len, &tp->chunk[i],
+                       &tp->splits[i]);
+    level_slots[nd.level] = std::max(level_slots[nd.level], tp->splits[i]);
+  }
+  int slots = 0;
+  for (int l = 0; l < TREE_MAX_LEVELS; l++) {
+    tp->level_slot0[l] = slots;
+    slots += level_slots[l];
+  }
+  tp->p.np_split = 0;
+  tp->p.n_naive = slots;
+  layout_workspace(&tp->p);
+  return TMLA_OK;
+}
+
+size_t typhoon_mla_decode_tree_workspace_bytes(const tmla_dims* dims, int32_t batch, int32_t q_len,
+                                               const tmla_prefix_node* nodes, int32_t num_nodes,
+                                               int32_t max_suffix_len) {
+  TreePlan tp;
+  if (make_tree_plan(dims, batch, q_len, nodes, num_nodes, max_suffix_len, 128, &tp) != TMLA_OK)
+    return 0;
+  const size_t a = tp.p.total;
+  make_tree_plan(dims, batch, q_len, nodes, num_nodes, max_suffix_len, 64, &tp);
+  return std::max(a, tp.p.total);
+}
+
+int typhoon_mla_decode_tree(const tmla_dims* dims, int32_t batch, int32_t q_len, const void* q,
+                            const tmla_prefix_node* nodes, int32_t num_nodes,
+                            const void* suffix_pool, int32_t num_blocks, int32_t block_size,
+                            const int32_t* block_table, int32_t max_blocks,
+                            const int32_t* suffix_lens, int32_t max_suffix_len, const void* w_uk,
+                            const void* w_uv, void* out, float* lse_out, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  if (block_size != 64 && block_size != 128) {
+    const int st0 = check_dims(dims);
+    return st0 != TMLA_OK ? st0 : TMLA_ERR_UNSUPPORTED;
+  }
+  TreePlan tp;
+  int st = make_tree_plan(dims, batch, q_len, nodes, num_nodes, max_suffix_len, block_size, &tp);
+  if (st != TMLA_OK) return st;
+  if (num_blocks < 0 || max_blocks < 0) return TMLA_ERR_INVALID_ARG;
+  if ((int64_t)max_blocks * block_size < max_suffix_len) return TMLA_ERR_INVALID_ARG;
+  if (batch == 0) return TMLA_OK;
+  if (!q || !out || !suffix_lens) return TMLA_ERR_INVALID_ARG;
+  const bool need_suffix = max_suffix_len > 0;
+  if (need_suffix && (!suffix_pool || !block_table || num_blocks == 0 || !w_uk || !w_uv))
+    return TMLA_ERR_INVALID_ARG;
+  const void* ptrs[] = {q, out, suffix_pool, w_uk, w_uv};
+  for (const void* ptr : ptrs)
+    if (ptr && misaligned(ptr, 16)) return TMLA_ERR_INVALID_ARG;
+  if (misaligned(block_table, 4) || misaligned(suffix_lens, 4) || misaligned(lse_out, 4))
+    return TMLA_ERR_INVALID_ARG;
+  for (int i = 0; i < num_nodes; i++)
+    if (tp.splits[i] > 0 && (!nodes[i].k || !nodes[i].v || misaligned(nodes[i].k, 16) ||
+                             misaligned(nodes[i].v, 16)))
+      return TMLA_ERR_INVALID_ARG;
+  const Plan& p = tp.p;
+  if (!workspace || misaligned(workspace, 256)) return TMLA_ERR_INVALID_ARG;
+  if (workspace_bytes < p.total) return TMLA_ERR_WORKSPACE_TOO_SMALL;
+
+  DecodeArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = q; a.suffix_pool = suffix_pool; a.block_table = block_table; a.suffix_lens = suffix_lens;
+  a.w_uk = w_uk; a.w_uv = w_uv; a.out = out; a.lse_out = lse_out; a.ws = (char*)workspace;
+  a.num_blocks = num_blocks; a.block_size = block_size; a.max_blocks = max_blocks;
+  a.sm_scale = dims->sm_scale; a.stream = (hipStream_t)stream;
+  const bool bf16 = dims->dtype == TMLA_BF16;
+  const size_t esz = bf16 ? 2 : 4;
+
+  (void)hipGetLastError();
+  // every level slot starts empty; a node's pass fills the rows of its own requests
+  launch_fill_f32((float*)(a.ws + p.off_naive_lse), (int64_t)p.n_naive * p.rows, -INFINITY, a.stream);
+  for (int i = 0; i < num_nodes; i++) {
+    if (tp.splits[i] == 0) continue;
+    const tmla_prefix_node& nd = nodes[i];
+    const int64_t row0 = (int64_t)nd.batch_begin * q_len * dims->num_heads;
+    const int64_t slot_row0 = (int64_t)tp.level_slot0[nd.level] * p.rows + row0;
+    Plan pn = p;                       // rows stays the stride between splits
+    pn.B = nd.batch_count; pn.Ls = nd.len; pn.p_chunk = tp.chunk[i]; pn.np_split = tp.splits[i];
+    pn.off_naive_o = p.off_naive_o + (size_t)slot_row0 * D_V * 4;
+    pn.off_naive_lse = p.off_naive_lse + (size_t)slot_row0 * 4;
+    DecodeArgs an = a;
+    an.q = (const char*)q + (size_t)row0 * D_QK * esz;
+    an.prefix_k = nd.k; an.prefix_v = nd.v;
+    if (bf16 && !(g_debug_flags & 1)) {
+      if ((st = mfma_prefix_attention(pn, an)) != TMLA_OK) return st;
+    } else if (bf16) {
+      simple_stage_naive<bf16_t>(pn, an, 0, pn.np_split, (int64_t)nd.batch_count * q_len * dims->num_heads);
+    } else {
+      simple_stage_naive<float>(pn, an, 0, pn.np_split, (int64_t)nd.batch_count * q_len * dims->num_heads);
+    }
+  }
+  if (!bf16) {
+    simple_stage_qabs<float>(p, a);
+    simple_stage_absorb<float>(p, a);
+    simple_stage_finalize<float>(p, a);
+  } else if (g_debug_flags & 1) {
+    simple_stage_qabs<bf16_t>(p, a);
+    simple_stage_absorb<bf16_t>(p, a);
+    simple_stage_finalize<bf16_t>(p, a);
+  } else {
+    if ((st = mfma_query_absorb(p, a)) != TMLA_OK) return st;
+    if ((st = mfma_absorb_attention(p, a)) != TMLA_OK) return st;
+    if ((st = mfma_finalize(p, a)) != TMLA_OK) return st;
   }
   return hipGetLastError() == hipSuccess ? TMLA_OK : TMLA_ERR_HIP;
 }

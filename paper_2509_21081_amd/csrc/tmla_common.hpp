@@ -102,7 +102,8 @@ template <typename T>
 void simple_expand(int H, int64_t ntok, const T* c, int64_t c_stride, const T* r, int64_t r_stride,
                    const T* w_uk, const T* w_uv, T* k_out, T* v_out, hipStream_t stream);
 template <typename T> void simple_stage_naive(const Plan& p, const DecodeArgs& a, int first_chunk,
-                                              int n_chunks);
+                                              int n_chunks, int64_t grid_rows = -1);
+void launch_fill_f32(float* p, int64_t n, float v, hipStream_t stream);
 template <typename T> void simple_stage_qabs(const Plan& p, const DecodeArgs& a);
 template <typename T> void simple_stage_absorb(const Plan& p, const DecodeArgs& a);
 template <typename T> void simple_stage_finalize(const Plan& p, const DecodeArgs& a);

@@ -302,11 +302,24 @@ simple_finalize_kernel(Plan p, const float* __restrict__ naive_o,
   if (lse_out && tid == 0) lse_out[row] = m + logf(z);
 }
 
+__global__ void fill_f32_kernel(float* p, int64_t n, float v) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+void launch_fill_f32(float* p, int64_t n, float v, hipStream_t stream) {
+  if (n <= 0) return;
+  hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p, n, v);
+}
+
+// `grid_rows` < 0: all p.rows rows; otherwise only the first grid_rows rows behind the (already
+// offset) query and partial pointers, p.rows staying the stride between chunks
 template <typename T>
-void simple_stage_naive(const Plan& p, const DecodeArgs& a, int first_chunk, int n_chunks) {
-  if (p.rows == 0 || n_chunks <= 0) return;
+void simple_stage_naive(const Plan& p, const DecodeArgs& a, int first_chunk, int n_chunks,
+                        int64_t grid_rows) {
+  if (grid_rows < 0) grid_rows = p.rows;
+  if (grid_rows == 0 || n_chunks <= 0) return;
   const int64_t pool_tokens = (int64_t)a.num_blocks * a.block_size;
-  hipLaunchKernelGGL(simple_naive_kernel<T>, dim3((unsigned)p.rows, n_chunks), dim3(NT), 0,
+  hipLaunchKernelGGL(simple_naive_kernel<T>, dim3((unsigned)grid_rows, n_chunks), dim3(NT), 0,
                      a.stream, p, (const T*)a.q, (const T*)a.prefix_k, (const T*)a.prefix_v,
                      (const T*)a.suffix_k_pool, (const T*)a.suffix_v_pool, a.block_table,
                      a.suffix_lens, a.max_blocks, a.block_size, pool_tokens, a.sm_scale,
@@ -336,7 +349,7 @@ void simple_stage_finalize(const Plan& p, const DecodeArgs& a) {
                      (const T*)a.w_uv, (T*)a.out, a.lse_out);
 }
 #define TMLA_INSTANTIATE(T)                                                        \
-  template void simple_stage_naive<T>(const Plan&, const DecodeArgs&, int, int);   \
+  template void simple_stage_naive<T>(const Plan&, const DecodeArgs&, int, int, int64_t);   \
   template void simple_stage_qabs<T>(const Plan&, const DecodeArgs&);              \
   template void simple_stage_absorb<T>(const Plan&, const DecodeArgs&);            \
   template void simple_stage_finalize<T>(const Plan&, const DecodeArgs&);

@@ -154,3 +154,39 @@ def test_auto_mode_threshold_follows_break_even_formula():
     assert big == T.typhoon_mla_decode_workspace_bytes(d, T.MODE_MIXED, 64, 1, 4096, 512)
     small = T.typhoon_mla_decode_workspace_bytes(d, T.MODE_AUTO, 2, 1, 4096, 512)
     assert small == T.typhoon_mla_decode_workspace_bytes(d, T.MODE_ABSORB_ONLY, 2, 1, 4096, 512)
+
+
+def test_tree_decode_validation():
+    import ctypes
+    L = T.lib()
+    d = _dims()
+    nul = ctypes.c_void_p(None)
+    one = ctypes.c_void_p(4096)   # never dereferenced: every case below fails validation first
+
+    def call(nodes, batch=4, q=one, ws=one, ws_bytes=1 << 30, block_size=64):
+        arr = T.make_nodes(nodes)
+        return L.typhoon_mla_decode_tree(ctypes.byref(d), batch, 1, q, arr, len(nodes), nul, 0,
+                                         block_size, nul, 0, one, 0, nul, nul, one, nul, ws,
+                                         ws_bytes, nul)
+
+    class P:   # stands in for a device tensor
+        def __init__(self, addr): self.addr = addr
+        def data_ptr(self): return self.addr
+    k = P(4096)
+    ok_nodes = [(k, k, 100, 0, 0, 4), (k, k, 50, 1, 0, 2), (k, k, 60, 1, 2, 2)]
+    assert T.typhoon_mla_decode_tree_workspace_bytes(d, 4, 1, ok_nodes, 0) > 0
+    assert call([], batch=0) == T.TMLA_OK                          # nothing to do
+    assert call(ok_nodes, batch=0) == T.TMLA_ERR_INVALID_ARG       # nodes outside the batch
+    assert call(ok_nodes, q=nul) == T.TMLA_ERR_INVALID_ARG
+    assert call(ok_nodes, ws_bytes=16) == T.TMLA_ERR_WORKSPACE_TOO_SMALL
+    assert call(ok_nodes, block_size=48) == T.TMLA_ERR_UNSUPPORTED
+    assert call([(k, k, 100, 0, 0, 4), (k, k, 50, 0, 3, 1)]) == T.TMLA_ERR_INVALID_ARG   # overlap
+    assert call([(k, k, 100, 8, 0, 4)]) == T.TMLA_ERR_INVALID_ARG                        # level
+    assert call([(k, k, 100, 0, 2, 3)]) == T.TMLA_ERR_INVALID_ARG                        # range
+    assert call([(k, k, -1, 0, 0, 4)]) == T.TMLA_ERR_INVALID_ARG
+    assert call([(None, None, 100, 0, 0, 4)]) == T.TMLA_ERR_INVALID_ARG                  # no K/V
+    assert call([(P(4100), k, 100, 0, 0, 4)]) == T.TMLA_ERR_INVALID_ARG                  # misaligned
+    # more levels need more partial slots
+    w1 = T.typhoon_mla_decode_tree_workspace_bytes(d, 4, 1, ok_nodes[:1], 64)
+    w2 = T.typhoon_mla_decode_tree_workspace_bytes(d, 4, 1, ok_nodes, 64)
+    assert 0 < w1 < w2
