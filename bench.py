@@ -83,6 +83,73 @@ def read_traffic(workload, kernel):
     return None
 
 
+def bench_tree(args, torch, T, C, W, dev):
+    """--workload "tree:B=64,H=128,L0=4096,G=4,L1=1024,Ln=512": a root prefix of L0 tokens shared by
+    all B requests, G groups of B/G requests sharing L1 more tokens each, Ln private suffix
+    tokens.  Timed: typhoon_mla_decode_tree, and beside it the flat alternative that shares only
+    the root and carries the group prefix in every request's suffix (typhoon_mla_decode, mixed)."""
+    kv = dict(item.split("=") for item in args.workload[5:].split(","))
+    B, H = int(kv["B"]), int(kv.get("H", 128))
+    L0, G, L1, Ln = int(kv.get("L0", 4096)), int(kv.get("G", 4)), int(kv.get("L1", 1024)), \
+        int(kv.get("Ln", 512))
+    assert B % G == 0
+    spec = W.WorkloadSpec(args.workload, "bf16", B, H, 1, L0, Ln, Ln, seed=9)
+    wl = W.make_workload(spec, poison=True)
+    d = wl.to(dev)
+    dims = T.make_dims(H, wl.sm_scale, "bf16")
+    pk, pv = T.typhoon_mla_expand_prefix(dims, d.prefix_ckv, d.prefix_krope, d.w_uk, d.w_uv)
+    nodes, keep = [(pk, pv, L0, 0, 0, B)], []
+    gen = torch.Generator().manual_seed(10)
+    for gi in range(G):
+        c = torch.randn((L1, 512), generator=gen).to(torch.bfloat16).to(dev)
+        r = torch.randn((L1, 64), generator=gen).to(torch.bfloat16).to(dev)
+        k, v = T.typhoon_mla_expand_prefix(dims, c, r, d.w_uk, d.w_uv)
+        keep.append((k, v))
+        nodes.append((k, v, L1, 1, gi * (B // G), B // G))
+    out = torch.empty((B, 1, H, 128), dtype=torch.bfloat16, device=dev)
+    lse = torch.empty((B, 1, H), dtype=torch.float32, device=dev)
+    ws = torch.empty(T.typhoon_mla_decode_tree_workspace_bytes(dims, B, 1, nodes, Ln),
+                     dtype=torch.uint8, device=dev)
+
+    def step_tree():
+        T.typhoon_mla_decode_tree(dims, d.q, nodes, suffix_pool=d.pool, block_table=d.block_table,
+                                  suffix_lens=d.suffix_lens, max_suffix_len=Ln, w_uk=d.w_uk,
+                                  w_uv=d.w_uv, out=out, lse_out=lse, workspace=ws)
+    ms_tree = time_steps(step_tree, args.steps, args.warmup, torch)
+    # flat alternative: same token counts, group prefix inside each request's suffix
+    flat = W.make_workload(W.WorkloadSpec("flat", "bf16", B, H, 1, L0, L1 + Ln, L1 + Ln, seed=9),
+                           poison=False).to(dev)
+    ws2 = torch.empty(T.typhoon_mla_decode_workspace_bytes(dims, T.MODE_MIXED, B, 1, L0, L1 + Ln),
+                      dtype=torch.uint8, device=dev)
+
+    def step_flat():
+        T.typhoon_mla_decode(dims, "mixed", flat.q, L0, prefix_k=pk, prefix_v=pv,
+                             suffix_pool=flat.pool, block_table=flat.block_table,
+                             suffix_lens=flat.suffix_lens, max_suffix_len=L1 + Ln, w_uk=d.w_uk,
+                             w_uv=d.w_uv, out=out, lse_out=lse, workspace=ws2)
+    ms_flat = time_steps(step_flat, max(3, args.steps // 2), max(1, args.warmup // 2), torch)
+    elem = 2
+    alg_bytes = ((L0 + G * L1) * H * 320 * elem + B * Ln * 576 * elem + B * H * (192 + 576) * elem
+                 + 2 * H * 128 * 512 * elem)
+    flops = 2 * B * H * ((L0 + L1) * 320 + Ln * 1088) + 4 * B * H * 128 * 512
+    t = ms_tree * 1e-3
+    print(json.dumps({
+        "metric": "MLA decode tokens/s (tree-shaped shared prefixes: naive per node + absorb "
+                  "suffix, one layer)",
+        "value": B / t, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_tree, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic (seeded N(0,1) latents and queries, N(0,0.02) up-projections)",
+        "config": {"workload": args.workload, "batch": B, "heads": H, "root_len": L0,
+                   "groups": G, "group_prefix_len": L1, "suffix_len": Ln},
+        "tflops": flops / t / 1e12,
+        "ms_flat_root_only_sharing": ms_flat, "speedup_vs_flat": ms_flat / ms_tree,
+        "roofline": {"kernel": "whole step", "bound": "hbm", "achieved": alg_bytes / t / 1e9,
+                     "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": alg_bytes / t / HBM_PEAK,
+                     "traffic": None, "algorithmic_bytes": alg_bytes},
+        "cpu_baseline": None}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -99,6 +166,8 @@ def main():
         sys.exit(1)
     T.lib()  # fail loudly if the HIP library is not built
     dev = torch.device("cuda:0")
+    if args.workload.startswith("tree:"):
+        return bench_tree(args, torch, T, C, W, dev)
     if args.workload in W.CONFIGS:
         spec = W.CONFIGS[args.workload]
     else:
