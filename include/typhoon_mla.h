@@ -214,6 +214,7 @@ int typhoon_mla_combine_lse(int32_t num_partials, int64_t rows, int32_t width,
  *     stages, for per-kernel timing -- 0x10 naive prefix attention, 0x20 naive suffix attention,
  *     0x40 query absorption, 0x80 absorb attention, 0x100 up-projection + combine.  The output
  *     is then meaningless unless the workspace still holds the other stages' results.
+ *   bit 9 (0x200): scalar kernel for the naive suffix attention of naive_only mode.
  * Returns the previous value.
  */
 int typhoon_mla_set_debug_flags(int flags);

@@ -318,7 +318,12 @@ int typhoon_mla_decode(const tmla_dims* dims, int32_t mode, int32_t batch, int32
       st = mfma_prefix_attention(p, a);
       if (st != TMLA_OK) return st;
     }
-    if (!only || (only & 0x20)) simple_stage_naive<bf16_t>(p, a, p.np_split, p.ns_chunks);
+    if (!only || (only & 0x20)) {
+      // (bit 9 of the debug flags keeps the scalar kernel for this stage)
+      if ((g_debug_flags & 0x200) || p.Sq > 64)
+        simple_stage_naive<bf16_t>(p, a, p.np_split, p.ns_chunks);
+      else if ((st = mfma_naive_suffix_attention(p, a)) != TMLA_OK) return st;
+    }
     if (!only || (only & 0x40)) {
       if (g_debug_flags & 2) simple_stage_qabs<bf16_t>(p, a);
       else if ((st = mfma_query_absorb(p, a)) != TMLA_OK) return st;

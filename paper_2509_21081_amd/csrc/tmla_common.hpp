@@ -113,6 +113,7 @@ int mfma_expand(int H, int64_t ntok, const void* c, int64_t c_stride, const void
                 int64_t r_stride, const void* w_uk, const void* w_uv, void* k_out, void* v_out,
                 hipStream_t stream);
 int mfma_prefix_attention(const Plan& p, const DecodeArgs& a);
+int mfma_naive_suffix_attention(const Plan& p, const DecodeArgs& a);
 int mfma_query_absorb(const Plan& p, const DecodeArgs& a);
 int mfma_absorb_attention(const Plan& p, const DecodeArgs& a);
 int mfma_absorb16_attention(const Plan& p, const DecodeArgs& a);   // S_q * H <= 16

@@ -33,10 +33,15 @@ struct PrefixArgs {
   int M, H, Ls, ntb, blocks_per_split;
   int64_t rows;
   float c;            // sm_scale * log2(e)
+  // paged per-request suffix (naive_only, Table 1 row "naive"): grid.y = request
+  const int32_t* block_table;
+  const int32_t* lens;
+  int max_blocks, page_shift;   // 32-token blocks per cache page = 1 << page_shift
+  int Sq, first_slot;           // partial slot of chunk 0
 };
 
 __device__ inline void load_q_frags(const PrefixArgs& a, int h, int q0, int n, int g,
-                                    bf16x8 (&qf)[2][12]) {
+                                    bf16x8 (&qf)[2][12], int q_end = 0x7fffffff) {
 #pragma unroll
   for (int nb = 0; nb < 2; nb++) {
     const int qi = q0 + nb * 32 + n;
@@ -44,7 +49,7 @@ __device__ inline void load_q_frags(const PrefixArgs& a, int h, int q0, int n, i
 #pragma unroll
     for (int ks = 0; ks < 12; ks++) {
       bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-      qf[nb][ks] = (qi < a.M) ? *(const bf16x8*)(p + 16 * ks) : z;
+      qf[nb][ks] = (qi < a.M && qi < q_end) ? *(const bf16x8*)(p + 16 * ks) : z;
     }
   }
 }
@@ -331,7 +336,7 @@ constexpr int TS_LDS_BYTES = TS_RING_BYTES > TS_MERGE_BYTES ? TS_RING_BYTES : TS
 // block (K fragments at [0, 12 KiB), V fragments behind them).
 __device__ inline void ts_block(uint32_t blk, int lane, const bf16x8 (&qf)[2][12],
                                 f32x16 (&o)[4][2], float (&m)[2], float (&l)[2], float c,
-                                int limit, int g) {
+                                const int (&limit)[2], int g, int nvalid = 32) {
   const uint32_t ka = blk + lane * 16;
   f32x16 sacc[2];
 #pragma unroll
@@ -369,7 +374,7 @@ __device__ inline void ts_block(uint32_t blk, int lane, const bf16x8 (&qf)[2][12
   for (int nb = 0; nb < 2; nb++) {
     bool rescale;
     const float alpha =
-        softmax_block(sacc[nb], m[nb], l[nb], c, limit, g, p[nb][0], p[nb][1], rescale);
+        softmax_block(sacc[nb], m[nb], l[nb], c, limit[nb], g, p[nb][0], p[nb][1], rescale);
     if (rescale) {
 #pragma unroll
       for (int db = 0; db < 4; db++) {
@@ -385,6 +390,19 @@ __device__ inline void ts_block(uint32_t blk, int lane, const bf16x8 (&qf)[2][12
   }
   lgkm_wait<0>(vf[0], vf[1], vf[2], vf[3]);
   lgkm_wait<0>(vf[4], vf[5], vf[6], vf[7]);
+  if (nvalid < 32) {
+    // a partial block of a paged cache: what lies behind its last token is not ours and need not
+    // be finite, and 0 * NaN would poison the product, so those V entries are cleared (element e
+    // of fragment kk holds token 16 kk + 8 (e / 4) + 4 g + e % 4, the order of the probabilities)
+#pragma unroll
+    for (int kk = 0; kk < 2; kk++)
+#pragma unroll
+      for (int e = 0; e < 8; e++)
+        if (acc_row(8 * kk + e, g) >= nvalid) {
+#pragma unroll
+          for (int db = 0; db < 4; db++) vf[kk * 4 + db][e] = (__bf16)0.f;
+        }
+  }
 #pragma unroll
   for (int kk = 0; kk < 2; kk++)
 #pragma unroll
@@ -394,14 +412,27 @@ __device__ inline void ts_block(uint32_t blk, int lane, const bf16x8 (&qf)[2][12
     }
 }
 
+// PAGED = false: the shared prefix, query block mb of all M queries, token split sp.
+// PAGED = true: the expanded paged suffix of request mb (naive_only mode): its S_q <= 64 queries,
+// token chunk sp of its own suffix, 32-token blocks located through the block table, causal mask
+// inside the suffix.  Same streaming and merge; grid.y = request.
+template <bool PAGED>
 __global__ void __launch_bounds__(256, 1) prefix_attn_token_split_kernel(PrefixArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int h = blockIdx.x, mb = blockIdx.y, sp = blockIdx.z;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, g = lane >> 5;
-  const int q0 = mb * 64;
+  const int q0 = PAGED ? mb * a.Sq : mb * 64;
+  const int q_end = PAGED ? q0 + a.Sq : a.M;
+  const int slot = PAGED ? a.first_slot + sp : sp;
+  int len = a.Ls;               // tokens this workgroup's queries can see at most
+  const int32_t* bt = nullptr;
+  if (PAGED) {
+    len = a.lens[mb];
+    bt = a.block_table + (size_t)mb * a.max_blocks;
+  }
 
   bf16x8 qf[2][12];
-  load_q_frags(a, h, q0, n, g, qf);
+  load_q_frags(a, h, q0, n, g, qf, q_end);
   // resident before the streamed loads start: no wait on them inside the loop
 #pragma unroll
   for (int nb = 0; nb < 2; nb++)
@@ -412,7 +443,7 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_token_split_kernel(PrefixA
                      "+v"(qf[nb][ks + 3])::"memory");
 
   const int tb0 = sp * a.blocks_per_split;
-  const int tb1 = min(a.ntb, tb0 + a.blocks_per_split);
+  const int tb1 = min(PAGED ? (len + TOK_BLK - 1) / TOK_BLK : a.ntb, tb0 + a.blocks_per_split);
   const __bf16* kbase = a.pk + ((size_t)h * a.ntb) * K_BLK_ELEMS + lane * 8;
   const __bf16* vbase = a.pv + ((size_t)h * a.ntb) * V_BLK_ELEMS + lane * 8;
 
@@ -428,10 +459,16 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_token_split_kernel(PrefixA
   // wavefront w streams blocks tb0 + w, tb0 + w + 4, ... through its private two-slot LDS ring
   char* ring = smem + wave * (2 * TS_BLOCK_BYTES);
   const uint32_t ring_addr = lds_addr(ring);
-  auto issue = [&](int tb, int slot) {
-    char* dst = ring + slot * TS_BLOCK_BYTES;
-    const __bf16* ks = kbase + (size_t)tb * K_BLK_ELEMS;
-    const __bf16* vs = vbase + (size_t)tb * V_BLK_ELEMS;
+  auto issue = [&](int tb, int rslot) {
+    char* dst = ring + rslot * TS_BLOCK_BYTES;
+    size_t ptb = tb;            // physical 32-token block
+    if (PAGED) {
+      // scalar load: a vector load here would have to be waited for with vmcnt(0)
+      const int page = scalar_load_i32(bt + (tb >> a.page_shift));
+      ptb = ((size_t)page << a.page_shift) + (tb & ((1 << a.page_shift) - 1));
+    }
+    const __bf16* ks = kbase + ptb * K_BLK_ELEMS;
+    const __bf16* vs = vbase + ptb * V_BLK_ELEMS;
 #pragma unroll
     for (int f = 0; f < 12; f++) dma16(ks + f * 512, dst + f * 1024);
 #pragma unroll
@@ -445,8 +482,15 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_token_split_kernel(PrefixA
     if (j + 1 < nmine) vm_wait<20>();   // block j has landed, block j+1 may still be in flight
     else vm_wait<0>();
     const int tb = first + 4 * j;
-    ts_block(ring_addr + (j & 1) * TS_BLOCK_BYTES, lane, qf, o, m, l, a.c,
-             min(32, a.Ls - tb * TOK_BLK), g);
+    int limit[2];
+#pragma unroll
+    for (int nb = 0; nb < 2; nb++) {
+      // PAGED: query s = nb * 32 + n of the request sees suffix tokens j <= len - S_q + s
+      const int vis = PAGED ? len - a.Sq + nb * 32 + n + 1 : len;
+      limit[nb] = min(32, vis - tb * TOK_BLK);
+    }
+    ts_block(ring_addr + (j & 1) * TS_BLOCK_BYTES, lane, qf, o, m, l, a.c, limit, g,
+             PAGED ? min(32, len - tb * TOK_BLK) : 32);
     if (j + 2 < nmine) issue(tb + 8, j & 1);
   }
   __syncthreads();   // the merge buffers below alias every wavefront's ring
@@ -492,17 +536,17 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_token_split_kernel(PrefixA
   for (int idx = tid; idx < 64 * 32; idx += 256) {
     const int qq = idx >> 5, c4 = idx & 31;
     const int qi = q0 + qq;
-    if (qi >= a.M) continue;
+    if (qi >= q_end) continue;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
     for (int w = 0; w < 4; w++) {
       const float4 x = *(const float4*)(sm_o + ((size_t)w * 64 + qq) * TS_ROW_FLOATS + c4 * 4);
       acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
     }
-    const size_t row = (size_t)sp * a.rows + (size_t)qi * a.H + h;
+    const size_t row = (size_t)slot * a.rows + (size_t)qi * a.H + h;
     *(float4*)(a.o + row * D_V + c4 * 4) = acc;
   }
-  if (tid < 64 && q0 + tid < a.M) {
+  if (tid < 64 && q0 + tid < q_end) {
     float ms = -INFINITY;
 #pragma unroll
     for (int w = 0; w < 4; w++) ms = fmaxf(ms, sm_m[w * 64 + tid]);
@@ -512,14 +556,14 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_token_split_kernel(PrefixA
       const float mw = sm_m[w * 64 + tid];
       lsum += (mw == -INFINITY) ? 0.f : sm_l[w * 64 + tid] * fast_exp2(mw - ms);
     }
-    const size_t row = (size_t)sp * a.rows + (size_t)(q0 + tid) * a.H + h;
+    const size_t row = (size_t)slot * a.rows + (size_t)(q0 + tid) * a.H + h;
     a.lse[row] = (lsum > 0.f) ? (ms + fast_log2(lsum)) * LN2 : -INFINITY;
   }
 }
 
 int mfma_prefix_attention(const Plan& p, const DecodeArgs& d) {
   if (p.np_split <= 0) return TMLA_OK;
-  PrefixArgs a;
+  PrefixArgs a = {};
   a.q = (const __bf16*)d.q;
   a.pk = (const __bf16*)d.prefix_k;
   a.pv = (const __bf16*)d.prefix_v;
@@ -534,7 +578,9 @@ int mfma_prefix_attention(const Plan& p, const DecodeArgs& d) {
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)prefix_attn_query_split_kernel<1>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, QS_LDS_BYTES) != hipSuccess ||
-        hipFuncSetAttribute((const void*)prefix_attn_token_split_kernel,
+        hipFuncSetAttribute((const void*)prefix_attn_token_split_kernel<false>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, TS_LDS_BYTES) != hipSuccess ||
+        hipFuncSetAttribute((const void*)prefix_attn_token_split_kernel<true>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, TS_LDS_BYTES) != hipSuccess)
       return TMLA_ERR_HIP;
     attr_set = true;
@@ -548,8 +594,39 @@ int mfma_prefix_attention(const Plan& p, const DecodeArgs& d) {
                        a);
   } else {
     dim3 grid(p.H, (a.M + 63) / 64, p.np_split);
-    hipLaunchKernelGGL(prefix_attn_token_split_kernel, grid, dim3(256), TS_LDS_BYTES, d.stream, a);
+    hipLaunchKernelGGL(prefix_attn_token_split_kernel<false>, grid, dim3(256), TS_LDS_BYTES, d.stream, a);
   }
+  return TMLA_OK;
+}
+
+// Naive attention over each request's own expanded paged suffix (naive_only mode): chunks of
+// p.ns_chunk tokens, partial slots [np_split, np_split + ns_chunks).
+int mfma_naive_suffix_attention(const Plan& p, const DecodeArgs& d) {
+  if (p.ns_chunks <= 0 || p.rows == 0) return TMLA_OK;
+  if (p.Sq > 64) return TMLA_ERR_UNSUPPORTED;
+  PrefixArgs a = {};
+  a.q = (const __bf16*)d.q;
+  a.pk = (const __bf16*)d.suffix_k_pool;
+  a.pv = (const __bf16*)d.suffix_v_pool;
+  a.o = (float*)(d.ws + p.off_naive_o);
+  a.lse = (float*)(d.ws + p.off_naive_lse);
+  a.M = p.B * p.Sq; a.H = p.H; a.Ls = 0;
+  a.ntb = (int)(((int64_t)d.num_blocks * d.block_size) / TOK_BLK);
+  a.blocks_per_split = p.ns_chunk / TOK_BLK;
+  a.rows = p.rows;
+  a.c = d.sm_scale * LOG2E;
+  a.block_table = d.block_table; a.lens = d.suffix_lens; a.max_blocks = d.max_blocks;
+  a.page_shift = d.block_size == 64 ? 1 : 2;
+  a.Sq = p.Sq; a.first_slot = p.np_split;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)prefix_attn_token_split_kernel<true>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, TS_LDS_BYTES) != hipSuccess)
+      return TMLA_ERR_HIP;
+    attr_set = true;
+  }
+  dim3 grid(p.H, p.B, p.ns_chunks);
+  hipLaunchKernelGGL(prefix_attn_token_split_kernel<true>, grid, dim3(256), TS_LDS_BYTES, d.stream, a);
   return TMLA_OK;
 }
 
