@@ -215,6 +215,9 @@ int typhoon_mla_combine_lse(int32_t num_partials, int64_t rows, int32_t width,
  *     0x40 query absorption, 0x80 absorb attention, 0x100 up-projection + combine.  The output
  *     is then meaningless unless the workspace still holds the other stages' results.
  *   bit 9 (0x200): scalar kernel for the naive suffix attention of naive_only mode.
+ *   bit 10 (0x400): naive prefix attention with more than 128 queries per head runs on the
+ *     8-wavefront kernel alone (otherwise it only redoes the workgroups in which the software-
+ *     pipelined kernel's fixed exponent references overflowed).
  * Returns the previous value.
  */
 int typhoon_mla_set_debug_flags(int flags);

@@ -61,7 +61,7 @@ __device__ inline int acc_row(int v, int g) { return 8 * (v >> 2) + 4 * g + (v &
 // Returns the factor by which the caller must rescale its output accumulators (1 if unchanged);
 // `rescale` is wave-uniform and tells whether any lane needs it.
 template <bool MASK = true>
-__device__ inline float softmax_block(f32x16& s, float& m, float& l, float c, int limit, int g,
+__device__ __forceinline__ float softmax_block(f32x16& s, float& m, float& l, float c, int limit, int g,
                                       bf16x8& p0, bf16x8& p1, bool& rescale) {
   if (MASK && limit < 32) {
 #pragma unroll

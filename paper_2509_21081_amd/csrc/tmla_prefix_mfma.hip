@@ -38,6 +38,9 @@ struct PrefixArgs {
   const int32_t* lens;
   int max_blocks, page_shift;   // 32-token blocks per cache page = 1 << page_shift
   int Sq, first_slot;           // partial slot of chunk 0
+  // query-split kernels: one flag per workgroup.  The pipelined kernel sets it when its result
+  // must be recomputed; the 8-wavefront kernel, launched behind it, returns at once where it is 0.
+  int* redo;
 };
 
 __device__ inline void load_q_frags(const PrefixArgs& a, int h, int q0, int n, int g,
@@ -132,6 +135,7 @@ __global__ void __launch_bounds__(512 / NB, 1) prefix_attn_query_split_kernel(Pr
   const int h = blockIdx.x, mb = blockIdx.y, sp = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  if (a.redo && a.redo[blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)] == 0) return;
   const int q0 = mb * QS_QUERIES + wave * (32 * NB);   // first query of this wavefront
 
   const int tb0 = sp * a.blocks_per_split;
@@ -304,6 +308,385 @@ __global__ void __launch_bounds__(512 / NB, 1) prefix_attn_query_split_kernel(Pr
 
 #pragma unroll
   for (int nb = 0; nb < NB; nb++) {
+    const int qi = q0 + nb * 32 + n;
+    const float lt = sum_halves(l[nb]);
+    if (qi >= a.M) continue;
+    const size_t row = (size_t)sp * a.rows + (size_t)qi * a.H + h;
+    if (lt > 0.f) {
+      const float inv = 1.f / lt;
+#pragma unroll
+      for (int db = 0; db < 4; db++)
+#pragma unroll
+        for (int v4 = 0; v4 < 4; v4++) {
+          float4 w = make_float4(o[db][nb][4 * v4] * inv, o[db][nb][4 * v4 + 1] * inv,
+                                 o[db][nb][4 * v4 + 2] * inv, o[db][nb][4 * v4 + 3] * inv);
+          *(float4*)(a.o + row * D_V + 32 * db + 8 * v4 + 4 * g) = w;
+        }
+      if (g == 0) a.lse[row] = (m[nb] + fast_log2(lt)) * LN2;
+    } else if (g == 0) {
+      a.lse[row] = -INFINITY;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ pipelined workgroup
+// 256 queries of a head per workgroup, four wavefronts (one per SIMD) of 64 queries each, so
+// every K/V fragment read from LDS feeds two MFMAs.  The instruction stream of a wavefront is
+// laid out by hand as one software pipeline: in period t it issues
+//     matrix core : scores of block t+1 (24 MFMAs), then P V of block t-1 (16 MFMAs)
+//     vector ALU  : softmax of block t, cut into 32 slices of three instructions, one slice
+//                   behind each of the first 32 MFMAs
+//     LDS         : one fragment read per MFMA pair, PL_D pairs ahead of its use (the reads run
+//                   on into the next period's first K fragments)
+//     global->LDS : this wavefront's five transfers of the period, one behind each of five MFMAs
+// so the vector work, the LDS latency and the transfer issue all hide under the matrix core.
+// K and V stream through separate rings because V of a block is needed two periods after its K:
+// period t issues K of block t + PL_AHEAD and V of block t + PL_AHEAD - 3 ("group" t + PL_AHEAD).
+// At the top of period t every wavefront waits for its own transfers of group t+2 and passes
+// the barrier; then K(t+1), the head of K(t+2) and V(t-1) are complete for everybody, and all
+// wavefronts have left period t-1, the last reader of K(t) and V(t-2), whose slots group
+// t + PL_AHEAD reuses.
+constexpr int PL_AHEAD = 8;
+constexpr int PL_NK = PL_AHEAD;                                   // K ring slots
+constexpr int PL_NV = PL_AHEAD - 1;                               // V ring slots
+constexpr int PL_K_BYTES = K_BLK_ELEMS * 2;                       // 12288
+constexpr int PL_V_BYTES = V_BLK_ELEMS * 2;                       // 8192
+constexpr int PL_V_BASE = PL_NK * PL_K_BYTES;                     // 98304
+constexpr int PL_LDS_BYTES = PL_V_BASE + PL_NV * PL_V_BYTES;      // 155648
+constexpr int PL_D = 6;                                           // fragment reads in flight
+constexpr int PL_QUERIES = 256;
+#define PL_SB() __builtin_amdgcn_sched_barrier(0)
+
+// The MFMAs of the pipelined loop are written in assembly to fix where their operands live:
+// scores accumulate in vector registers (the softmax reads them), outputs and the resident Q
+// fragments in accumulation registers (only the matrix core touches them), so no copies between
+// the two register files appear in the loop.  The assembler cannot see that these statements
+// are MFMAs: every vector-ALU read of their results below is either a whole period away or
+// preceded by pl_mfma_drain().
+__device__ inline void pl_mfma_s_first(f32x16& d, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+}
+__device__ inline void pl_mfma_s(f32x16& d, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+}
+__device__ inline void pl_mfma_o(f32x16& d, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b));
+}
+// enough idle issue slots for the last MFMA (16 passes) to have written its result
+__device__ inline void pl_mfma_drain() {
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");
+}
+
+__global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int h = blockIdx.x, mb = blockIdx.y, sp = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int q0 = mb * PL_QUERIES + wave * 64;   // first query of this wavefront
+
+  const int tb0 = sp * a.blocks_per_split;
+  const int tb1 = min(a.ntb, tb0 + a.blocks_per_split);
+  const int nblk = tb1 - tb0;
+  // the very last block of the prefix may be partial; it gets a masked pass after the loop
+  const bool has_tail = (tb1 == a.ntb) && (a.Ls % TOK_BLK != 0) && nblk > 0;
+  const int nfull = has_tail ? nblk - 1 : nblk;
+  const int tail_limit = a.Ls - (tb0 + nblk - 1) * TOK_BLK;   // valid tokens of a partial tail
+  const uint32_t lane_addr = lds_addr(smem) + lane * 16;
+
+  bf16x8 qf[2][12];
+#pragma unroll
+  for (int nb = 0; nb < 2; nb++) {
+    const int qi = q0 + nb * 32 + n;
+    const __bf16* p = a.q + ((size_t)qi * a.H + h) * D_QK + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < 12; ks++) {
+      bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+      qf[nb][ks] = (qi < a.M) ? *(const bf16x8*)(p + 16 * ks) : z;
+    }
+  }
+#pragma unroll
+  for (int nb = 0; nb < 2; nb++)
+#pragma unroll
+    for (int ks = 0; ks < 12; ks += 4)
+      asm volatile("s_waitcnt vmcnt(0)"
+                   : "+a"(qf[nb][ks]), "+a"(qf[nb][ks + 1]), "+a"(qf[nb][ks + 2]),
+                     "+a"(qf[nb][ks + 3])::"memory");
+
+  // transfers: fragment f of a block is moved by wavefront f % 4 (K: 12 fragments, V: 8)
+  const char* kbase = (const char*)(a.pk + ((size_t)h * a.ntb + tb0) * K_BLK_ELEMS);
+  const char* vbase = (const char*)(a.pv + ((size_t)h * a.ntb + tb0) * V_BLK_ELEMS);
+  const uint32_t lane_off = wave * 1024 + lane * 16;
+  auto dma_k = [&](int k, int f) __attribute__((always_inline)) {
+    if (k < nblk)
+      dma16(kbase + (size_t)k * PL_K_BYTES + f * 4096 + lane_off,
+            smem + (k % PL_NK) * PL_K_BYTES + f * 4096 + wave * 1024);
+  };
+  auto dma_v = [&](int kv, int f) __attribute__((always_inline)) {
+    if (kv >= 0 && kv < nblk)
+      dma16(vbase + (size_t)kv * PL_V_BYTES + f * 4096 + lane_off,
+            smem + PL_V_BASE + (kv % PL_NV) * PL_V_BYTES + f * 4096 + wave * 1024);
+  };
+  for (int k = 0; k < PL_AHEAD - 1; k++) {
+    dma_k(k, 0); dma_k(k, 1); dma_k(k, 2);
+    dma_v(k - 3, 0); dma_v(k - 3, 1);
+  }
+
+  f32x16 o[4][2];
+#pragma unroll
+  for (int db = 0; db < 4; db++)
+#pragma unroll
+    for (int nb = 0; nb < 2; nb++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) o[db][nb][v] = 0.f;
+  // Softmax bookkeeping.  The exponent reference m of a query is fixed once, to the maximum of
+  // its scores over the first block of this split, and never moved inside the loop: the
+  // result does not depend on the reference (numerator and denominator share it), only the
+  // float range does.  Scores more than ~2^7 (log2 units) above the first block's maximum
+  // would overflow; that shows as a denominator that is not a moderate finite number, is
+  // checked once at the end, and sends the whole workgroup to the fallback kernel.
+  float m[2] = {0.f, 0.f}, l[2] = {0.f, 0.f};
+  const float c = a.c;
+
+  // top of period t: groups t+3 .. t+PL_AHEAD-1 may still be in flight, group t+2 must have
+  // landed.  Group k holds three transfers of K(k) if k < nblk and two of V(k-3) if
+  // 0 <= k-3 < nblk.
+  auto sync = [&](int t) __attribute__((always_inline)) {
+    const int lo = t + 3, hi = t + PL_AHEAD - 1;
+    const int nk = max(0, min(hi, nblk - 1) - max(lo, 0) + 1);
+    const int nv = max(0, min(hi, nblk + 2) - max(lo, 3) + 1);
+    const int pend = 3 * nk + 2 * nv;
+    static_assert(PL_AHEAD == 8, "the waits below assume five groups in flight");
+    if (__builtin_expect(pend >= 25, 1)) vm_wait<25>();
+    else if (pend >= 20) vm_wait<20>();
+    else if (pend >= 15) vm_wait<15>();
+    else if (pend >= 10) vm_wait<10>();
+    else if (pend >= 5) vm_wait<5>();
+    else vm_wait<0>();
+    raw_barrier();
+  };
+
+  bf16x8 fr[8];          // fragment ring: fragment j of period t lives in fr[(4 (t & 1) + j) % 8]
+  f32x16 sb[2][2];       // scores of blocks of even / odd index
+  bf16x8 pb[2][2][2];    // probabilities of blocks of even / odd index
+#pragma unroll
+  for (int i = 0; i < 8; i++)
+#pragma unroll
+    for (int e = 0; e < 8; e++) (&pb[0][0][0])[i][e] = (__bf16)0.f;
+
+  // Period t = 0 .. nfull.  The instruction stream is the same for every period; at the two ends
+  // some of it runs on data that is not there, arranged to be harmless:
+  //   * scores of a block t+1 > nfull multiply whatever the ring holds; nobody reads them;
+  //   * the softmax pieces of block t = nfull (the partial tail, or nothing) produce
+  //     probabilities nobody reads, and their sum is dropped;
+  //   * P V of block -1 (period 0) multiplies the all-zero initial probabilities with the K
+  //     fragments of block 0 standing in for V, which adds exact zeros.
+  auto period = [&](int t, auto par_tag) __attribute__((always_inline)) {
+    constexpr int PAR = decltype(par_tag)::value;
+    f32x16 (&s_in)[2] = sb[PAR];
+    f32x16 (&s_out)[2] = sb[PAR ^ 1];
+    bf16x8 (&p_out)[2][2] = pb[PAR];
+    bf16x8 (&p_in)[2][2] = pb[PAR ^ 1];
+
+    sync(t);
+    const uint32_t ka1 = lane_addr + ((t + 1) % PL_NK) * PL_K_BYTES;   // K(t+1)
+    const uint32_t ka2 = lane_addr + ((t + 2) % PL_NK) * PL_K_BYTES;   // K(t+2)
+    const uint32_t va =                                                // V(t-1), or K(0)
+        lane_addr + (t >= 1 ? PL_V_BASE + ((t - 1) % PL_NV) * PL_V_BYTES : 0);
+    const int kg = t + PL_AHEAD;      // group issued in this period
+
+    float xa = 0.f, xb = 0.f, ea = 0.f, eb = 0.f;
+    float sum[2] = {0.f, 0.f};
+    // The softmax of block t, two scores (one packed pair of probabilities) per quantum, spread
+    // so that no instruction waits for the one before it and no transcendental directly follows
+    // an MFMA (either would cost idle issue slots):
+    //   behind the first MFMA of quantum j : arguments of pair j; pack the pair of quantum j-1
+    //   behind the second MFMA             : sum += e_a(j-1); e_a = exp2; sum += e_b(j-1); e_b = exp2
+    // Pair k = elements 2 (k % 8), 2 (k % 8) + 1 of column block k / 8.  The empty statements pin
+    // every piece where it is written (the results are only used much later, and would
+    // otherwise be moved down there).
+    auto part1 = [&](auto j_tag) __attribute__((always_inline)) {
+      constexpr int j = decltype(j_tag)::value;
+      float xa_new = 0.f, xb_new = 0.f;
+      if constexpr (j < 16) {
+        constexpr int nb = j / 8, v0 = 2 * (j % 8);
+        xa_new = __builtin_fmaf(s_in[nb][v0], c, -m[nb]);
+        xb_new = __builtin_fmaf(s_in[nb][v0 + 1], c, -m[nb]);
+        asm volatile("" : "+v"(xa_new), "+v"(xb_new));
+        PL_SB();
+      }
+      if constexpr (j >= 1 && j <= 16) {
+        constexpr int nb = (j - 1) / 8, v0 = 2 * ((j - 1) % 8);
+        const bf16x2 pk = {(__bf16)ea, (__bf16)eb};
+        p_out[nb][v0 / 8][v0 % 8] = pk[0];
+        p_out[nb][v0 / 8][v0 % 8 + 1] = pk[1];
+        asm volatile("" : "+v"(p_out[nb][v0 / 8]));
+      }
+      xa = xa_new;
+      xb = xb_new;
+    };
+    auto part2 = [&](auto j_tag) __attribute__((always_inline)) {
+      constexpr int j = decltype(j_tag)::value;
+      constexpr bool prev = j >= 1 && j <= 16, cur = j < 16;
+      constexpr int nbp = prev ? (j - 1) / 8 : 0;
+      if constexpr (prev) {
+        sum[nbp] += ea;
+        asm volatile("" : "+v"(sum[nbp]));
+        PL_SB();
+      }
+      if constexpr (cur) {
+        ea = fast_exp2(xa);
+        asm volatile("" : "+v"(ea));
+        PL_SB();
+      }
+      if constexpr (prev) {
+        sum[nbp] += eb;
+        asm volatile("" : "+v"(sum[nbp]));
+        PL_SB();
+      }
+      if constexpr (cur) {
+        eb = fast_exp2(xb);
+        asm volatile("" : "+v"(eb));
+      }
+    };
+    auto dma = [&](auto i_tag) __attribute__((always_inline)) {
+      constexpr int i = decltype(i_tag)::value;
+      if constexpr (i < 3) dma_k(kg, i);
+      else dma_v(kg - 3, i - 3);
+    };
+
+    static_for<20>([&](auto j_tag) {
+      constexpr int j = decltype(j_tag)::value;
+      constexpr int cur = (4 * PAR + j) % 8;
+      if constexpr ((j & 1) == 0) {
+        // fragments j + PL_D and j + PL_D + 1 are requested, fragments j and j + 1 awaited
+        static_for<2>([&](auto i_tag) {
+          constexpr int jn = j + PL_D + decltype(i_tag)::value;
+          constexpr int nxt = (4 * PAR + jn) % 8;
+          if constexpr (jn < 12) fr[nxt] = lds_read_b128<1024 * jn>(ka1);
+          else if constexpr (jn < 20) fr[nxt] = lds_read_b128<1024 * (jn - 12)>(va);
+          else fr[nxt] = lds_read_b128<1024 * (jn - 20)>(ka2);
+        });
+        lgkm_wait<PL_D>(fr[cur], fr[(cur + 1) % 8]);
+      }
+      PL_SB();
+      static_for<2>([&](auto nb_tag) {
+        constexpr int nb = decltype(nb_tag)::value;
+        if constexpr (j == 0) {
+          pl_mfma_s_first(s_out[nb], fr[cur], qf[nb][j]);
+        } else if constexpr (j < 12) {
+          pl_mfma_s(s_out[nb], fr[cur], qf[nb][j]);
+        } else {
+          constexpr int kk = (j - 12) / 4, db = (j - 12) % 4;
+          pl_mfma_o(o[db][nb], fr[cur], p_in[nb][kk]);
+        }
+        PL_SB();
+        if constexpr (nb == 0) part1(j_tag);
+        else part2(j_tag);
+        if constexpr (j % 4 == 0 && nb == 0) dma(std::integral_constant<int, j / 4>{});
+        PL_SB();
+      });
+    });
+    if (t < nfull) {
+      l[0] += sum[0];
+      l[1] += sum[1];
+    }
+  };
+
+  // maximum of this lane's query over the first `limit` tokens of a block of scores, scaled
+  auto block_max = [&](const f32x16& s, int limit) __attribute__((always_inline)) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 16; v++)
+      if (acc_row(v, g) < limit) mx = fmaxf(mx, s[v]);
+    return max_halves(mx) * c;
+  };
+
+  using P0 = std::integral_constant<int, 0>;
+  using P1 = std::integral_constant<int, 1>;
+  if (nblk > 0) {
+    // before period 0: the scores of block 0 and from them the exponent references, the first
+    // fragments of K(1), group PL_AHEAD - 1
+    sync(-1);
+    {
+      const uint32_t ka0 = lane_addr, ka1 = lane_addr + PL_K_BYTES;
+      static_for<12>([&](auto j_tag) {
+        constexpr int j = decltype(j_tag)::value;
+        fr[j % 8] = lds_read_b128<1024 * j>(ka0);
+        lgkm_wait<0>(fr[j % 8]);
+        static_for<2>([&](auto nb_tag) {
+          constexpr int nb = decltype(nb_tag)::value;
+          if constexpr (j == 0) pl_mfma_s_first(sb[0][nb], fr[j % 8], qf[nb][j]);
+          else pl_mfma_s(sb[0][nb], fr[j % 8], qf[nb][j]);
+        });
+      });
+      static_for<PL_D>([&](auto j_tag) {
+        constexpr int j = decltype(j_tag)::value;
+        fr[j] = lds_read_b128<1024 * j>(ka1);
+      });
+      const int k = PL_AHEAD - 1;
+      dma_k(k, 0); dma_k(k, 1); dma_k(k, 2);
+      dma_v(k - 3, 0); dma_v(k - 3, 1);
+      pl_mfma_drain();
+      const int limit0 = nfull > 0 ? 32 : tail_limit;
+      m[0] = block_max(sb[0][0], limit0);
+      m[1] = block_max(sb[0][1], limit0);
+    }
+    for (int t = 0; t <= nfull; t += 2) {
+      period(t, P0{});
+      if (t + 1 <= nfull) period(t + 1, P1{});
+    }
+    lgkm_wait<0>();
+    pl_mfma_drain();
+  }
+  if (has_tail) {
+    // The scores of the partial last block were formed by the loop's last period (or above, if
+    // the block is the only one).  Masked probabilities against the same references, then P V.
+    vm_wait<0>();
+    raw_barrier();
+    auto tail = [&](auto par_tag) __attribute__((always_inline)) {
+      constexpr int PAR = decltype(par_tag)::value;
+      bf16x8 pt[2][2];
+#pragma unroll
+      for (int nb = 0; nb < 2; nb++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) {
+          const float e = acc_row(v, g) < tail_limit
+                              ? fast_exp2(__builtin_fmaf(sb[PAR][nb][v], c, -m[nb])) : 0.f;
+          l[nb] += e;
+          pt[nb][v / 8][v % 8] = (__bf16)e;
+        }
+      const uint32_t va = lane_addr + PL_V_BASE + ((nblk - 1) % PL_NV) * PL_V_BYTES;
+      bf16x8 vf[8];
+      static_for<8>([&](auto j) { vf[j] = lds_read_b128<1024 * decltype(j)::value>(va); });
+      lgkm_wait<0>(vf[0], vf[1], vf[2], vf[3]);
+      lgkm_wait<0>(vf[4], vf[5], vf[6], vf[7]);
+#pragma unroll
+      for (int kk = 0; kk < 2; kk++)
+#pragma unroll
+        for (int db = 0; db < 4; db++)
+#pragma unroll
+          for (int nb = 0; nb < 2; nb++) pl_mfma_o(o[db][nb], vf[kk * 4 + db], pt[nb][kk]);
+      pl_mfma_drain();
+    };
+    if (nfull & 1) tail(P1{});
+    else tail(P0{});
+  }
+
+  // a denominator that is not a moderate finite number: the fixed references did not hold
+  const bool bad_lane = !(l[0] < 0x1p100f) || !(l[1] < 0x1p100f);
+  const bool bad_wave = __builtin_amdgcn_ballot_w64(bad_lane) != 0;
+  if (a.redo) {
+    int* flags = (int*)smem;
+    __syncthreads();   // every transfer has landed and every ring read is done
+    if (lane == 0) flags[wave] = bad_wave ? 1 : 0;
+    __syncthreads();
+    if (tid == 0)
+      a.redo[blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)] =
+          flags[0] | flags[1] | flags[2] | flags[3];
+  }
+
+#pragma unroll
+  for (int nb = 0; nb < 2; nb++) {
     const int qi = q0 + nb * 32 + n;
     const float lt = sum_halves(l[nb]);
     if (qi >= a.M) continue;
@@ -585,7 +968,22 @@ int mfma_prefix_attention(const Plan& p, const DecodeArgs& d) {
       return TMLA_ERR_HIP;
     attr_set = true;
   }
-  if (a.M > 128) {
+  if (a.M > 128 && !(debug_flags() & 0x400)) {
+    static bool pl_attr = false;
+    if (!pl_attr) {
+      if (hipFuncSetAttribute((const void*)prefix_attn_pipelined_kernel,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, PL_LDS_BYTES) != hipSuccess)
+        return TMLA_ERR_HIP;
+      pl_attr = true;
+    }
+    // The pipelined kernel first; the 8-wavefront kernel (which moves its exponent references
+    // as it goes) behind it on the same grid, doing work only where the first one gave up.
+    dim3 grid(p.H, (a.M + PL_QUERIES - 1) / PL_QUERIES, p.np_split);
+    a.redo = (int*)(d.ws + p.off_prefix_redo);
+    hipLaunchKernelGGL(prefix_attn_pipelined_kernel, grid, dim3(256), PL_LDS_BYTES, d.stream, a);
+    hipLaunchKernelGGL(prefix_attn_query_split_kernel<1>, grid, dim3(512), QS_LDS_BYTES, d.stream,
+                       a);
+  } else if (a.M > 128) {
     dim3 grid(p.H, (a.M + QS_QUERIES - 1) / QS_QUERIES, p.np_split);
     // NB = 1 measured faster than NB = 2 on every configuration: vector-ALU and matrix-core
     // instructions of a SIMD issue serially, so hiding LDS and barrier latency with a second

@@ -91,6 +91,50 @@ def test_forced_small_chunks(case, mode, gpu_device, monkeypatch):
                      logit_gain=wl.spec.q_gain)
 
 
+@pytest.mark.parametrize("flags", [0, 0x400], ids=["pipelined", "8-wave"])
+@pytest.mark.parametrize("prefix_len", [31, 32, 40, 288, 1024, 1100])
+def test_pipelined_prefix_kernel_long_runs(prefix_len, flags, gpu_device, monkeypatch):
+    """More than 128 queries per head select the software-pipelined prefix kernel; one split
+    (forced) makes a single workgroup walk the whole prefix: a partial block only, one full
+    block, full + partial, one block more than the transfer look-ahead, and long runs with and
+    without a partial tail.  Also with the 8-wavefront kernel, its fallback, running alone."""
+    monkeypatch.setenv("TMLA_PREFIX_SPLITS", "1")
+    spec = W.small_spec(name=f"pipe_{prefix_len}", dtype="bf16", batch=200, heads=16, q_len=1,
+                        prefix_len=prefix_len, suffix_min=0, suffix_max=40, seed=41 + prefix_len)
+    wl = W.make_workload(spec)
+    ref, ref_lse = O.mla_decode_definition(**wl.as_float64())
+    print(f"pipelined prefix, prefix_len={prefix_len} flags={flags}", flush=True)
+    got, got_lse = Hh.run_library(wl, "mixed", gpu_device, flags=flags)
+    Hh.assert_parity(got, got_lse, ref, ref_lse, "bf16", f"pipe_{prefix_len}")
+
+
+@pytest.mark.parametrize("gain,first", [(256.0, 64), (256.0, 1000), (16.0, 64), (1.0 / 64.0, 64)])
+def test_prefix_scores_far_from_the_first_block(gain, first, gpu_device, monkeypatch):
+    """The RoPE part of the keys from token `first` on is scaled by `gain` (a power of two, and
+    that part of a key is stored as given, so the oracle sees exactly what the kernels see): the
+    scores there lie far above (or below) those of the first block, whose maximum the pipelined
+    kernel takes as its exponent reference.  With gain 256 its denominators overflow for every
+    query: it must notice, and the 8-wavefront kernel behind it must redo every workgroup,
+    which makes the result bit-identical to that kernel running alone (debug flag 0x400)."""
+    monkeypatch.setenv("TMLA_PREFIX_SPLITS", "1")
+    spec = W.small_spec(name="growth", dtype="bf16", batch=150, heads=16, q_len=1,
+                        prefix_len=1100, suffix_min=0, suffix_max=30, seed=77)
+    wl = W.make_workload(spec)
+    wl.prefix_krope[first:] *= gain
+    ref, ref_lse = O.mla_decode_definition(**wl.as_float64())
+    print(f"prefix score growth, gain={gain} from token {first}", flush=True)
+    got, got_lse = Hh.run_library(wl, "mixed", gpu_device)
+    alone, alone_lse = Hh.run_library(wl, "mixed", gpu_device, flags=0x400)
+    # peaked rows: the bf16 rounding of the one dominant probability and the fp32 rounding of
+    # large scores go straight into the LSE
+    lg = max(1.0, gain / 4.0)
+    Hh.assert_parity(got, got_lse, ref, ref_lse, "bf16", f"growth_{gain}_{first}", logit_gain=lg)
+    Hh.assert_parity(alone, alone_lse, ref, ref_lse, "bf16", f"growth_{gain}_{first}/8-wave",
+                     logit_gain=lg)
+    if gain >= 256.0:
+        assert np.array_equal(got, alone) and np.array_equal(got_lse, alone_lse)
+
+
 @pytest.mark.parametrize("flags", [0, 1], ids=["mfma", "scalar"])
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 @pytest.mark.parametrize("ntok", [1, 31, 64, 100, 300])
