@@ -348,11 +348,12 @@ __global__ void __launch_bounds__(512 / NB, 1) prefix_attn_query_split_kernel(Pr
 // t + PL_AHEAD reuses.
 constexpr int PL_AHEAD = 8;
 constexpr int PL_NK = PL_AHEAD;                                   // K ring slots
-constexpr int PL_NV = PL_AHEAD - 1;                               // V ring slots
+constexpr int PL_NV = 8;                                          // V ring slots (7 needed)
 constexpr int PL_K_BYTES = K_BLK_ELEMS * 2;                       // 12288
 constexpr int PL_V_BYTES = V_BLK_ELEMS * 2;                       // 8192
 constexpr int PL_V_BASE = PL_NK * PL_K_BYTES;                     // 98304
-constexpr int PL_LDS_BYTES = PL_V_BASE + PL_NV * PL_V_BYTES;      // 155648
+constexpr int PL_LDS_BYTES = PL_V_BASE + PL_NV * PL_V_BYTES;      // 163840 = all of LDS
+static_assert((PL_NK & (PL_NK - 1)) == 0 && (PL_NV & (PL_NV - 1)) == 0, "slot = block & (n - 1)");
 constexpr int PL_D = 6;                                           // fragment reads in flight
 constexpr int PL_QUERIES = 256;
 #define PL_SB() __builtin_amdgcn_sched_barrier(0)
@@ -375,6 +376,15 @@ __device__ inline void pl_mfma_o(f32x16& d, const bf16x8& a, const bf16x8& b) {
 // enough idle issue slots for the last MFMA (16 passes) to have written its result
 __device__ inline void pl_mfma_drain() {
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");
+}
+// 64 lanes x 16 bytes from `base` (wave-uniform, in scalar registers) + `lane_off` (per lane) to
+// 1 KiB of LDS at the wave-uniform byte address `lds`.  Written out so that the address is the
+// scalar-base form (no 64-bit vector additions per transfer).  The statement sets M0 behind
+// the compiler's back, which is safe only because this kernel issues every global-to-LDS
+// transfer through it and uses nothing else that reads M0.
+__device__ inline void pl_dma16(uint32_t lane_off, const void* base, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               ::"v"(lane_off), "s"(base), "s"(lds) : "memory");
 }
 
 __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArgs a) {
@@ -415,20 +425,25 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
   // transfers: fragment f of a block is moved by wavefront f % 4 (K: 12 fragments, V: 8)
   const char* kbase = (const char*)(a.pk + ((size_t)h * a.ntb + tb0) * K_BLK_ELEMS);
   const char* vbase = (const char*)(a.pv + ((size_t)h * a.ntb + tb0) * V_BLK_ELEMS);
-  const uint32_t lane_off = wave * 1024 + lane * 16;
-  auto dma_k = [&](int k, int f) __attribute__((always_inline)) {
-    if (k < nblk)
-      dma16(kbase + (size_t)k * PL_K_BYTES + f * 4096 + lane_off,
-            smem + (k % PL_NK) * PL_K_BYTES + f * 4096 + wave * 1024);
+  const uint32_t lds_base = lds_addr(smem) + wave * 1024;
+  uint32_t lane_off[3];   // fragment w, w + 4, w + 8 of a block
+#pragma unroll
+  for (int f = 0; f < 3; f++) lane_off[f] = f * 4096 + wave * 1024 + lane * 16;
+  using GUARD = std::true_type;
+  using NOGUARD = std::false_type;
+  auto dma_k = [&](int k, int f, auto guard_tag) __attribute__((always_inline)) {
+    if (!decltype(guard_tag)::value || k < nblk)
+      pl_dma16(lane_off[f], kbase + (size_t)k * PL_K_BYTES,
+               lds_base + (k & (PL_NK - 1)) * PL_K_BYTES + f * 4096);
   };
-  auto dma_v = [&](int kv, int f) __attribute__((always_inline)) {
-    if (kv >= 0 && kv < nblk)
-      dma16(vbase + (size_t)kv * PL_V_BYTES + f * 4096 + lane_off,
-            smem + PL_V_BASE + (kv % PL_NV) * PL_V_BYTES + f * 4096 + wave * 1024);
+  auto dma_v = [&](int kv, int f, auto guard_tag) __attribute__((always_inline)) {
+    if (!decltype(guard_tag)::value || (kv >= 0 && kv < nblk))
+      pl_dma16(lane_off[f], vbase + (size_t)kv * PL_V_BYTES,
+               lds_base + PL_V_BASE + (kv & (PL_NV - 1)) * PL_V_BYTES + f * 4096);
   };
   for (int k = 0; k < PL_AHEAD - 1; k++) {
-    dma_k(k, 0); dma_k(k, 1); dma_k(k, 2);
-    dma_v(k - 3, 0); dma_v(k - 3, 1);
+    dma_k(k, 0, GUARD{}); dma_k(k, 1, GUARD{}); dma_k(k, 2, GUARD{});
+    dma_v(k - 3, 0, GUARD{}); dma_v(k - 3, 1, GUARD{});
   }
 
   f32x16 o[4][2];
@@ -438,6 +453,11 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
     for (int nb = 0; nb < 2; nb++)
 #pragma unroll
       for (int v = 0; v < 16; v++) o[db][nb][v] = 0.f;
+  // (pins the zeroing here: moved down next to the first MFMA that accumulates into them, the
+  // register writes would sit closer to it than the hardware allows without wait states, which
+  // nobody inserts in front of an MFMA written in assembly)
+  asm volatile("" : "+a"(o[0][0]), "+a"(o[1][0]), "+a"(o[2][0]), "+a"(o[3][0]), "+a"(o[0][1]),
+                    "+a"(o[1][1]), "+a"(o[2][1]), "+a"(o[3][1]));
   // Softmax bookkeeping.  The exponent reference m of a query is fixed once, to the maximum of
   // its scores over the first block of this split, and never moved inside the loop: the
   // result does not depend on the reference (numerator and denominator share it), only the
@@ -450,18 +470,22 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
   // top of period t: groups t+3 .. t+PL_AHEAD-1 may still be in flight, group t+2 must have
   // landed.  Group k holds three transfers of K(k) if k < nblk and two of V(k-3) if
   // 0 <= k-3 < nblk.
-  auto sync = [&](int t) __attribute__((always_inline)) {
-    const int lo = t + 3, hi = t + PL_AHEAD - 1;
-    const int nk = max(0, min(hi, nblk - 1) - max(lo, 0) + 1);
-    const int nv = max(0, min(hi, nblk + 2) - max(lo, 3) + 1);
-    const int pend = 3 * nk + 2 * nv;
+  auto sync = [&](int t, auto steady_tag) __attribute__((always_inline)) {
     static_assert(PL_AHEAD == 8, "the waits below assume five groups in flight");
-    if (__builtin_expect(pend >= 25, 1)) vm_wait<25>();
-    else if (pend >= 20) vm_wait<20>();
-    else if (pend >= 15) vm_wait<15>();
-    else if (pend >= 10) vm_wait<10>();
-    else if (pend >= 5) vm_wait<5>();
-    else vm_wait<0>();
+    if constexpr (decltype(steady_tag)::value) {
+      vm_wait<25>();
+    } else {
+      const int lo = t + 3, hi = t + PL_AHEAD - 1;
+      const int nk = max(0, min(hi, nblk - 1) - max(lo, 0) + 1);
+      const int nv = max(0, min(hi, nblk + 2) - max(lo, 3) + 1);
+      const int pend = 3 * nk + 2 * nv;
+      if (pend >= 25) vm_wait<25>();
+      else if (pend >= 20) vm_wait<20>();
+      else if (pend >= 15) vm_wait<15>();
+      else if (pend >= 10) vm_wait<10>();
+      else if (pend >= 5) vm_wait<5>();
+      else vm_wait<0>();
+    }
     raw_barrier();
   };
 
@@ -472,6 +496,11 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
   for (int i = 0; i < 8; i++)
 #pragma unroll
     for (int e = 0; e < 8; e++) (&pb[0][0][0])[i][e] = (__bf16)0.f;
+  // (from here on these zeros are values in registers like any other: known to be zero, they
+  // would be re-created right in front of the MFMA that reads them, closer than the hardware
+  // allows without wait states, which nobody inserts in front of an MFMA written in assembly)
+  asm volatile("" : "+v"(pb[0][0][0]), "+v"(pb[0][0][1]), "+v"(pb[0][1][0]), "+v"(pb[0][1][1]),
+                    "+v"(pb[1][0][0]), "+v"(pb[1][0][1]), "+v"(pb[1][1][0]), "+v"(pb[1][1][1]));
 
   // Period t = 0 .. nfull.  The instruction stream is the same for every period; at the two ends
   // some of it runs on data that is not there, arranged to be harmless:
@@ -480,18 +509,21 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
   //     probabilities nobody reads, and their sum is dropped;
   //   * P V of block -1 (period 0) multiplies the all-zero initial probabilities with the K
   //     fragments of block 0 standing in for V, which adds exact zeros.
-  auto period = [&](int t, auto par_tag) __attribute__((always_inline)) {
+  // STEADY: 2 <= t and t + PL_AHEAD < nblk -- every block and transfer the period touches exists,
+  // so the guards and the count of transfers in flight are compile-time facts.
+  auto period = [&](int t, auto par_tag, auto steady_tag) __attribute__((always_inline)) {
     constexpr int PAR = decltype(par_tag)::value;
+    constexpr bool STEADY = decltype(steady_tag)::value;
     f32x16 (&s_in)[2] = sb[PAR];
     f32x16 (&s_out)[2] = sb[PAR ^ 1];
     bf16x8 (&p_out)[2][2] = pb[PAR];
     bf16x8 (&p_in)[2][2] = pb[PAR ^ 1];
 
-    sync(t);
-    const uint32_t ka1 = lane_addr + ((t + 1) % PL_NK) * PL_K_BYTES;   // K(t+1)
-    const uint32_t ka2 = lane_addr + ((t + 2) % PL_NK) * PL_K_BYTES;   // K(t+2)
+    sync(t, steady_tag);
+    const uint32_t ka1 = lane_addr + ((t + 1) & (PL_NK - 1)) * PL_K_BYTES;   // K(t+1)
+    const uint32_t ka2 = lane_addr + ((t + 2) & (PL_NK - 1)) * PL_K_BYTES;   // K(t+2)
     const uint32_t va =                                                // V(t-1), or K(0)
-        lane_addr + (t >= 1 ? PL_V_BASE + ((t - 1) % PL_NV) * PL_V_BYTES : 0);
+        lane_addr + (STEADY || t >= 1 ? PL_V_BASE + ((t - 1) & (PL_NV - 1)) * PL_V_BYTES : 0);
     const int kg = t + PL_AHEAD;      // group issued in this period
 
     float xa = 0.f, xb = 0.f, ea = 0.f, eb = 0.f;
@@ -550,8 +582,8 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
     };
     auto dma = [&](auto i_tag) __attribute__((always_inline)) {
       constexpr int i = decltype(i_tag)::value;
-      if constexpr (i < 3) dma_k(kg, i);
-      else dma_v(kg - 3, i - 3);
+      if constexpr (i < 3) dma_k(kg, i, std::integral_constant<bool, !STEADY>{});
+      else dma_v(kg - 3, i - 3, std::integral_constant<bool, !STEADY>{});
     };
 
     static_for<20>([&](auto j_tag) {
@@ -586,7 +618,10 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
         PL_SB();
       });
     });
-    if (t < nfull) {
+    // Control flow joins below and at the top of the next period, and register copies may be
+    // placed there; the last MFMAs must have written their results before any such copy.
+    pl_mfma_drain();
+    if (STEADY || t < nfull) {
       l[0] += sum[0];
       l[1] += sum[1];
     }
@@ -606,7 +641,7 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
   if (nblk > 0) {
     // before period 0: the scores of block 0 and from them the exponent references, the first
     // fragments of K(1), group PL_AHEAD - 1
-    sync(-1);
+    sync(-1, NOGUARD{});
     {
       const uint32_t ka0 = lane_addr, ka1 = lane_addr + PL_K_BYTES;
       static_for<12>([&](auto j_tag) {
@@ -624,16 +659,25 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
         fr[j] = lds_read_b128<1024 * j>(ka1);
       });
       const int k = PL_AHEAD - 1;
-      dma_k(k, 0); dma_k(k, 1); dma_k(k, 2);
-      dma_v(k - 3, 0); dma_v(k - 3, 1);
+      dma_k(k, 0, GUARD{}); dma_k(k, 1, GUARD{}); dma_k(k, 2, GUARD{});
+      dma_v(k - 3, 0, GUARD{}); dma_v(k - 3, 1, GUARD{});
       pl_mfma_drain();
       const int limit0 = nfull > 0 ? 32 : tail_limit;
       m[0] = block_max(sb[0][0], limit0);
       m[1] = block_max(sb[0][1], limit0);
     }
-    for (int t = 0; t <= nfull; t += 2) {
-      period(t, P0{});
-      if (t + 1 <= nfull) period(t + 1, P1{});
+    using ST = std::true_type;
+    using GN = std::false_type;
+    period(0, P0{}, GN{});
+    if (1 <= nfull) period(1, P1{}, GN{});
+    int t = 2;
+    for (; t + 1 + PL_AHEAD < nblk; t += 2) {
+      period(t, P0{}, ST{});
+      period(t + 1, P1{}, ST{});
+    }
+    for (; t <= nfull; t += 2) {
+      period(t, P0{}, GN{});
+      if (t + 1 <= nfull) period(t + 1, P1{}, GN{});
     }
     lgkm_wait<0>();
     pl_mfma_drain();
@@ -655,7 +699,7 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
           l[nb] += e;
           pt[nb][v / 8][v % 8] = (__bf16)e;
         }
-      const uint32_t va = lane_addr + PL_V_BASE + ((nblk - 1) % PL_NV) * PL_V_BYTES;
+      const uint32_t va = lane_addr + PL_V_BASE + ((nblk - 1) & (PL_NV - 1)) * PL_V_BYTES;
       bf16x8 vf[8];
       static_for<8>([&](auto j) { vf[j] = lds_read_b128<1024 * decltype(j)::value>(va); });
       lgkm_wait<0>(vf[0], vf[1], vf[2], vf[3]);
