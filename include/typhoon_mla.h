@@ -218,6 +218,9 @@ int typhoon_mla_combine_lse(int32_t num_partials, int64_t rows, int32_t width,
  *   bit 10 (0x400): naive prefix attention with more than 128 queries per head runs on the
  *     8-wavefront kernel alone (otherwise it only redoes the workgroups in which the software-
  *     pipelined kernel's fixed exponent references overflowed).
+ *   bit 11 (0x800): the absorb attention kernel for more than 32 query rows per request walks
+ *     every chunk with moving exponent references (otherwise only chunks in which its first walk,
+ *     with references fixed at the chunk's first tokens, overflowed).
  * Returns the previous value.
  */
 int typhoon_mla_set_debug_flags(int flags);

@@ -22,6 +22,13 @@
 //   barrier C   every wavefront reads the 8 probability fragments (4 k-steps x 2 query blocks)
 //   and accumulates its latent quarter.
 // The denominators stay split by token half until the end and are summed through LDS.
+//
+// The chunk is first walked with FIXED exponent references: they are set once, to the maxima of
+// step 0, so from step 1 on the maxima, their exchange, barrier B and the rescale all disappear
+// (the result does not depend on the reference, only the float range does: scores about 2^7
+// log2-units above the first step's maximum overflow).  If the denominators end up outside a
+// moderate finite range, the workgroup walks the chunk again with the lazy moving references
+// described above.
 #include "tmla_absorb_tile.hpp"
 
 namespace tmla {
@@ -35,6 +42,7 @@ constexpr int A64_LDS_BYTES = A64_MAX_OFF + A64_MAX_BYTES; // 160256 <= 160 KiB
 struct Absorb64Args {
   AbsorbArgs a;
   int nqg, n_lat, B;
+  int moving_only;   // debug: skip the walk with fixed references
 };
 
 __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
@@ -187,244 +195,271 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
   }
   // (barrier A of step 0 also tells that every wavefront has its fragments: slots 2, 3 are free)
 
-  f32x16 o[4][2];   // [latent block of the own quarter][query block]
-#pragma unroll
-  for (int mb = 0; mb < 4; mb++)
-#pragma unroll
-    for (int q = 0; q < 2; q++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) o[mb][q][v] = 0.f;
-  float m[2] = {-INFINITY, -INFINITY};   // exponent references of column n in either query block
-  float l = 0.f;                         // denominator part: own query block, own token half
+  // One walk over the chunk; `first` = step 0 is already on its way (issued above with the
+  // query blocks).  Returns false if the walk used fixed references and they did not hold.
+  auto walk = [&](auto fixed_tag, bool first) __attribute__((always_inline)) -> bool {
+    constexpr bool FIXED = decltype(fixed_tag)::value;
+    if (!first) {
+      RowSrc s0, s1;
+      step_src(0, s0, s1);
+      issue_all(s0, smem, dl);
+      issue_all(s1, smem + AB_TILE_BYTES, dl);
+    }
+    f32x16 o[4][2];   // [latent block of the own quarter][query block]
+  #pragma unroll
+    for (int mb = 0; mb < 4; mb++)
+  #pragma unroll
+      for (int q = 0; q < 2; q++)
+  #pragma unroll
+        for (int v = 0; v < 16; v++) o[mb][q][v] = 0.f;
+    float m[2] = {-INFINITY, -INFINITY};   // exponent references of column n in either query block
+    float m_use[2] = {0.f, 0.f};           // the same, 0 where no token is visible
+    float l = 0.f;                         // denominator part: own query block, own token half
 
-  for (int step = 0; step < nstep; step++) {
-    vm_wait<0>();
-    raw_barrier();   // A
-    const bool do_pf = step + 1 < nstep;
-    RowSrc pf0, pf1;
-    if (do_pf) step_src(step + 1, pf0, pf1);
-    char* pf_dst = smem + (((step + 1) & 1) * 2) * AB_TILE_BYTES;
-    const uint32_t sbase = smem_base + ((step & 1) * 2) * AB_TILE_BYTES;   // the step's two tiles
+    for (int step = 0; step < nstep; step++) {
+      vm_wait<0>();
+      raw_barrier();   // A
+      const bool do_pf = step + 1 < nstep;
+      RowSrc pf0, pf1;
+      if (do_pf) step_src(step + 1, pf0, pf1);
+      char* pf_dst = smem + (((step + 1) & 1) * 2) * AB_TILE_BYTES;
+      const uint32_t sbase = smem_base + ((step & 1) * 2) * AB_TILE_BYTES;   // the step's two tiles
 
-    // ---- scores: own token half, own query block
-    const uint32_t tbase = sbase + th * AB_TILE_BYTES;
-    const uint32_t sa = tbase + s_off;
-    f32x16 sacc;
-#pragma unroll
-    for (int v = 0; v < 16; v++) sacc[v] = 0.f;
-    {
-      // 9 groups of 4 k-steps (the last one is the rope part); three fragment buffers in
-      // rotation keep two groups of LDS reads in flight behind the one feeding the MFMAs
-      bf16x8 f[3][4];
-      auto rd = [&](auto gsel, auto dsel) __attribute__((always_inline)) {
-        constexpr int G = decltype(gsel)::value;
-        constexpr int D = decltype(dsel)::value;
-        if constexpr (G < 8) {
-          static_for<4>([&](auto j) {
-            f[D][j] = lds_read_b128<32 * (4 * G + decltype(j)::value)>(sa);
-          });
-        } else {
-          static_for<4>([&](auto j) {
-            f[D][j] = lds_read_b128<0>(tbase + r_off[decltype(j)::value]);
-          });
-        }
-      };
-      rd(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-      rd(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
-      static_for<9>([&](auto grp) {
-        constexpr int G = decltype(grp)::value;
-        constexpr int cur = G % 3;
-        if constexpr (G + 2 < 9) {
-          rd(std::integral_constant<int, G + 2>{}, std::integral_constant<int, (G + 2) % 3>{});
-          lgkm_wait<8>(f[cur][0], f[cur][1], f[cur][2], f[cur][3]);
-        } else if constexpr (G + 1 < 9) {
-          lgkm_wait<4>(f[cur][0], f[cur][1], f[cur][2], f[cur][3]);
-        } else {
-          lgkm_wait<0>(f[cur][0], f[cur][1], f[cur][2], f[cur][3]);
-        }
-        static_for<4>([&](auto j) {
-          sacc = mfma32(f[cur][j], qf[4 * G + decltype(j)::value], sacc);
-        });
-        // The next step's transfers.  A transfer holds up the issuing wavefront while the
-        // memory pipeline takes it, and longer when other wavefronts present theirs at the same
-        // time, so the wavefronts take turns: wavefront w issues in groups w and w + 4 (a whole
-        // tile each), wavefront 0, which has three groups (0, 4, 8), a third of its 18 in each.
-        if (do_pf) {
-          if constexpr (G == 0 || G == 4 || G == 8) {
-            if (wave == 0) {
-              static_for<6>([&](auto i_) {
-                constexpr int k = (G / 4) * 6 + decltype(i_)::value;   // 0 .. 17
-                if constexpr (k < 9) issue_part<k>(pf0, pf_dst, dl);
-                else issue_part<k - 9>(pf1, pf_dst + AB_TILE_BYTES, dl);
-              });
-            }
-          } else if constexpr (G < 4) {
-            if (wave == G) issue_all(pf0, pf_dst, dl);
+      // ---- scores: own token half, own query block
+      const uint32_t tbase = sbase + th * AB_TILE_BYTES;
+      const uint32_t sa = tbase + s_off;
+      f32x16 sacc;
+  #pragma unroll
+      for (int v = 0; v < 16; v++) sacc[v] = 0.f;
+      {
+        // 9 groups of 4 k-steps (the last one is the rope part); three fragment buffers in
+        // rotation keep two groups of LDS reads in flight behind the one feeding the MFMAs
+        bf16x8 f[3][4];
+        auto rd = [&](auto gsel, auto dsel) __attribute__((always_inline)) {
+          constexpr int G = decltype(gsel)::value;
+          constexpr int D = decltype(dsel)::value;
+          if constexpr (G < 8) {
+            static_for<4>([&](auto j) {
+              f[D][j] = lds_read_b128<32 * (4 * G + decltype(j)::value)>(sa);
+            });
           } else {
-            if (wave == G - 4) issue_all(pf1, pf_dst + AB_TILE_BYTES, dl);
+            static_for<4>([&](auto j) {
+              f[D][j] = lds_read_b128<0>(tbase + r_off[decltype(j)::value]);
+            });
           }
+        };
+        rd(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        rd(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
+        static_for<9>([&](auto grp) {
+          constexpr int G = decltype(grp)::value;
+          constexpr int cur = G % 3;
+          if constexpr (G + 2 < 9) {
+            rd(std::integral_constant<int, G + 2>{}, std::integral_constant<int, (G + 2) % 3>{});
+            lgkm_wait<8>(f[cur][0], f[cur][1], f[cur][2], f[cur][3]);
+          } else if constexpr (G + 1 < 9) {
+            lgkm_wait<4>(f[cur][0], f[cur][1], f[cur][2], f[cur][3]);
+          } else {
+            lgkm_wait<0>(f[cur][0], f[cur][1], f[cur][2], f[cur][3]);
+          }
+          static_for<4>([&](auto j) {
+            sacc = mfma32(f[cur][j], qf[4 * G + decltype(j)::value], sacc);
+          });
+          // The next step's transfers.  A transfer holds up the issuing wavefront while the
+          // memory pipeline takes it, and longer when other wavefronts present theirs at the same
+          // time, so the wavefronts take turns: wavefront w issues in groups w and w + 4 (a whole
+          // tile each), wavefront 0, which has three groups (0, 4, 8), a third of its 18 in each.
+          if (do_pf) {
+            if constexpr (G == 0 || G == 4 || G == 8) {
+              if (wave == 0) {
+                static_for<6>([&](auto i_) {
+                  constexpr int k = (G / 4) * 6 + decltype(i_)::value;   // 0 .. 17
+                  if constexpr (k < 9) issue_part<k>(pf0, pf_dst, dl);
+                  else issue_part<k - 9>(pf1, pf_dst + AB_TILE_BYTES, dl);
+                });
+              }
+            } else if constexpr (G < 4) {
+              if (wave == G) issue_all(pf0, pf_dst, dl);
+            } else {
+              if (wave == G - 4) issue_all(pf1, pf_dst + AB_TILE_BYTES, dl);
+            }
+          }
+        });
+      }
+
+      // ---- local maxima -> LDS
+      const int limit = min(32, vis_q - (t0 + step * 64 + th * 32));
+      if (limit < 32) {
+  #pragma unroll
+        for (int v = 0; v < 16; v++)
+          if (acc_row(v, g) >= limit) sacc[v] = -INFINITY;
+      }
+      if (!FIXED || step == 0) {
+        {
+          float mx = sacc[0];
+#pragma unroll
+          for (int v = 1; v < 16; v++) mx = fmaxf(mx, sacc[v]);
+          mx = max_halves(mx) * a.c;
+          if (g == 0) lds_write_b32(mx_wr, mx);
         }
-      });
-    }
+        lgkm_wait<0>();
+        raw_barrier();   // B
 
-    // ---- local maxima -> LDS
-    const int limit = min(32, vis_q - (t0 + step * 64 + th * 32));
-    if (limit < 32) {
-#pragma unroll
-      for (int v = 0; v < 16; v++)
-        if (acc_row(v, g) >= limit) sacc[v] = -INFINITY;
-    }
-    {
-      float mx = sacc[0];
-#pragma unroll
-      for (int v = 1; v < 16; v++) mx = fmaxf(mx, sacc[v]);
-      mx = max_halves(mx) * a.c;
-      if (g == 0) lds_write_b32(mx_wr, mx);
-    }
-    lgkm_wait<0>();
-    raw_barrier();   // B
-
-    // ---- common exponent references, probabilities -> LDS
-    f32x4 mm = lds_read_f32x4(mx_rd);   // [wave] = [qb + 2 * th]
-    lgkm_wait<0>(mm);
-    float m_use[2], alpha[2];
-    bool grow = false;
-#pragma unroll
-    for (int q = 0; q < 2; q++) {
-      const float bm = fmaxf(mm[q], mm[q + 2]);
-      const float m_new = (bm > m[q] + RESCALE_TAU) ? bm : m[q];
-      m_use[q] = (m_new == -INFINITY) ? 0.f : m_new;
-      grow = grow || (m_new > m[q]);
-      alpha[q] = m[q] - m_use[q];   // exponent of the rescale factor (m = -inf -> factor 0)
-      m[q] = m_new;
-    }
-    // (in step 0 every accumulator is still zero: nothing to rescale)
-    if (step > 0 && __builtin_amdgcn_ballot_w64(grow) != 0) {
-      alpha[0] = fast_exp2(alpha[0]);
-      alpha[1] = fast_exp2(alpha[1]);
-      l *= alpha[qb];
-#pragma unroll
-      for (int mb = 0; mb < 4; mb++)
+        // ---- common exponent references
+        f32x4 mm = lds_read_f32x4(mx_rd);   // [wave] = [qb + 2 * th]
+        lgkm_wait<0>(mm);
+        float alpha[2];
+        bool grow = false;
 #pragma unroll
         for (int q = 0; q < 2; q++) {
-          // the accumulators live in accumulation registers, which the vector ALU cannot address;
-          // routing them through this statement keeps their copies inside the rare branch
-          // (otherwise the copies out are hoisted and run in every step)
-          asm volatile("" : "+a"(o[mb][q]));
-#pragma unroll
-          for (int v = 0; v < 16; v++) o[mb][q][v] *= alpha[q];
-          asm volatile("" : "+a"(o[mb][q]));
+          const float bm = fmaxf(mm[q], mm[q + 2]);
+          const float m_new = (bm > m[q] + RESCALE_TAU) ? bm : m[q];
+          m_use[q] = (m_new == -INFINITY) ? 0.f : m_new;
+          grow = grow || (m_new > m[q]);
+          alpha[q] = m[q] - m_use[q];   // exponent of the rescale factor (m = -inf -> factor 0)
+          m[q] = m_new;
         }
-    }
-    {
-      const float mu = m_use[qb];
-      bf16x8 p0, p1;
-      float sum = 0.f;
+        // (in step 0 every accumulator is still zero: nothing to rescale)
+        if (!FIXED && step > 0 && __builtin_amdgcn_ballot_w64(grow) != 0) {
+          alpha[0] = fast_exp2(alpha[0]);
+          alpha[1] = fast_exp2(alpha[1]);
+          l *= alpha[qb];
 #pragma unroll
-      for (int v = 0; v < 8; v++) {
-        const float p = fast_exp2(__builtin_fmaf(sacc[v], a.c, -mu));
-        sum += p;
-        p0[v] = (__bf16)p;
-      }
+          for (int mb = 0; mb < 4; mb++)
 #pragma unroll
-      for (int v = 0; v < 8; v++) {
-        const float p = fast_exp2(__builtin_fmaf(sacc[8 + v], a.c, -mu));
-        sum += p;
-        p1[v] = (__bf16)p;
-      }
-      l += sum;
-      lds_write_b128<0>(p_wr, p0);
-      lds_write_b128<1024>(p_wr, p1);
-    }
-    // the first group of transposed cache fragments does not depend on the probabilities: it is
-    // requested before barrier C (the probability writes were issued earlier and complete first)
-    const uint32_t va = sbase + v_off;
-    short4v lo[2][4], hi[2][4];
-    auto rdv = [&](auto grp_, auto buf_) __attribute__((always_inline)) {
-      constexpr int G = decltype(grp_)::value;   // = mb
-      constexpr int D = decltype(buf_)::value;
-      static_for<4>([&](auto ks_) {
-        constexpr int ks = decltype(ks_)::value;
-        constexpr int thp = ks >> 1, kk = ks & 1;
-        constexpr int off = thp * AB_TILE_BYTES + (16 * kk) * AB_ROW_BYTES + 64 * G;
-        lo[D][ks] = lds_read_tr16_b64<off>(va);
-        hi[D][ks] = lds_read_tr16_b64<off + 8 * AB_ROW_BYTES>(va);
-      });
-    };
-    rdv(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-    lgkm_wait<8>();
-    raw_barrier();   // C
-
-    // ---- outputs: own latent quarter, all 64 tokens, both query blocks
-    {
-      // k-step ks = 2 * th' + kk: 16 tokens of tile th'; probability fragments [ks][query block]
-      bf16x8 pf[4][2];
-      static_for<4>([&](auto ks_) {
-        constexpr int ks = decltype(ks_)::value;
-        constexpr int thp = ks >> 1, kk = ks & 1;
-        pf[ks][0] = lds_read_b128<(0 + 2 * thp) * 2048 + kk * 1024>(p_rd);
-        pf[ks][1] = lds_read_b128<(1 + 2 * thp) * 2048 + kk * 1024>(p_rd);
-      });
-      // transposed cache fragments: one group per latent block mb (4 k-steps, 8 reads), double
-      // buffered; each fragment feeds the MFMAs of both query blocks
-      static_for<4>([&](auto ks_) {
-        constexpr int ks = decltype(ks_)::value;
-        lgkm_wait<0>(pf[ks][0], pf[ks][1]);
-      });
-      static_for<4>([&](auto mb_) {
-        constexpr int mb = decltype(mb_)::value;
-        constexpr int cur = mb & 1, nxt = cur ^ 1;
-        if constexpr (mb + 1 < 4) {
-          rdv(std::integral_constant<int, mb + 1>{}, std::integral_constant<int, nxt>{});
-          lgkm_wait<8>(lo[cur][0], lo[cur][1], lo[cur][2], lo[cur][3]);
-          lgkm_wait<8>(hi[cur][0], hi[cur][1], hi[cur][2], hi[cur][3]);
-        } else {
-          lgkm_wait<0>(lo[cur][0], lo[cur][1], lo[cur][2], lo[cur][3]);
-          lgkm_wait<0>(hi[cur][0], hi[cur][1], hi[cur][2], hi[cur][3]);
+            for (int q = 0; q < 2; q++) {
+              // the accumulators live in accumulation registers, which the vector ALU cannot
+              // address; routing them through this statement keeps their copies inside the rare
+              // branch (otherwise the copies out are hoisted and run in every step)
+              asm volatile("" : "+a"(o[mb][q]));
+#pragma unroll
+              for (int v = 0; v < 16; v++) o[mb][q][v] *= alpha[q];
+              asm volatile("" : "+a"(o[mb][q]));
+            }
         }
+      }
+      // ---- probabilities -> LDS
+      {
+        const float mu = m_use[qb];
+        bf16x8 p0, p1;
+        float sum = 0.f;
+  #pragma unroll
+        for (int v = 0; v < 8; v++) {
+          const float p = fast_exp2(__builtin_fmaf(sacc[v], a.c, -mu));
+          sum += p;
+          p0[v] = (__bf16)p;
+        }
+  #pragma unroll
+        for (int v = 0; v < 8; v++) {
+          const float p = fast_exp2(__builtin_fmaf(sacc[8 + v], a.c, -mu));
+          sum += p;
+          p1[v] = (__bf16)p;
+        }
+        l += sum;
+        lds_write_b128<0>(p_wr, p0);
+        lds_write_b128<1024>(p_wr, p1);
+      }
+      // the first group of transposed cache fragments does not depend on the probabilities: it is
+      // requested before barrier C (the probability writes were issued earlier and complete first)
+      const uint32_t va = sbase + v_off;
+      short4v lo[2][4], hi[2][4];
+      auto rdv = [&](auto grp_, auto buf_) __attribute__((always_inline)) {
+        constexpr int G = decltype(grp_)::value;   // = mb
+        constexpr int D = decltype(buf_)::value;
         static_for<4>([&](auto ks_) {
           constexpr int ks = decltype(ks_)::value;
-          const bf16x8 af = join_tr(lo[cur][ks], hi[cur][ks]);
-          o[mb][0] = mfma32(af, pf[ks][0], o[mb][0]);
-          o[mb][1] = mfma32(af, pf[ks][1], o[mb][1]);
+          constexpr int thp = ks >> 1, kk = ks & 1;
+          constexpr int off = thp * AB_TILE_BYTES + (16 * kk) * AB_ROW_BYTES + 64 * G;
+          lo[D][ks] = lds_read_tr16_b64<off>(va);
+          hi[D][ks] = lds_read_tr16_b64<off + 8 * AB_ROW_BYTES>(va);
         });
-      });
-    }
-  }
+      };
+      rdv(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+      lgkm_wait<8>();
+      raw_barrier();   // C
 
-  // ---- denominators: sum the two token halves of either query block through LDS
-  raw_barrier();   // everyone is past its last read of the maxima buffer
-  {
-    const float lh = sum_halves(l);
-    if (g == 0) lds_write_b32(mx_wr, lh);
-  }
-  lgkm_wait<0>();
-  raw_barrier();
-  f32x4 ll = lds_read_f32x4(mx_rd);
-  lgkm_wait<0>(ll);
-#pragma unroll
-  for (int q = 0; q < 2; q++) {
-    const int r_local = (qg * 2 + q) * 32 + n;
-    if (r_local >= a.R) continue;
-    const int64_t row = (int64_t)b * a.R + r_local;
-    const float lt = ll[q] + ll[q + 2];
-    float* l_dst = a.lat_lse + (size_t)item * a.rows + row;
-    if (lt > 0.f) {
-      const float inv = 1.f / lt;
-      __bf16* o_dst = a.lat_o + ((size_t)item * a.rows + row) * D_L + 128 * wave + 4 * g;
-#pragma unroll
-      for (int mb = 0; mb < 4; mb++)
-#pragma unroll
-        for (int v4 = 0; v4 < 4; v4++) {
-          bf16x4 w;
-#pragma unroll
-          for (int e = 0; e < 4; e++) w[e] = (__bf16)(o[mb][q][4 * v4 + e] * inv);
-          *(bf16x4*)(o_dst + 32 * mb + 8 * v4) = w;
-        }
-      if (wave == q && g == 0) *l_dst = (m[q] + fast_log2(lt)) * LN2;
-    } else if (wave == q && g == 0) {
-      *l_dst = -INFINITY;   // the causal mask hid every token of this chunk from this query
+      // ---- outputs: own latent quarter, all 64 tokens, both query blocks
+      {
+        // k-step ks = 2 * th' + kk: 16 tokens of tile th'; probability fragments [ks][query block]
+        bf16x8 pf[4][2];
+        static_for<4>([&](auto ks_) {
+          constexpr int ks = decltype(ks_)::value;
+          constexpr int thp = ks >> 1, kk = ks & 1;
+          pf[ks][0] = lds_read_b128<(0 + 2 * thp) * 2048 + kk * 1024>(p_rd);
+          pf[ks][1] = lds_read_b128<(1 + 2 * thp) * 2048 + kk * 1024>(p_rd);
+        });
+        // transposed cache fragments: one group per latent block mb (4 k-steps, 8 reads), double
+        // buffered; each fragment feeds the MFMAs of both query blocks
+        static_for<4>([&](auto ks_) {
+          constexpr int ks = decltype(ks_)::value;
+          lgkm_wait<0>(pf[ks][0], pf[ks][1]);
+        });
+        static_for<4>([&](auto mb_) {
+          constexpr int mb = decltype(mb_)::value;
+          constexpr int cur = mb & 1, nxt = cur ^ 1;
+          if constexpr (mb + 1 < 4) {
+            rdv(std::integral_constant<int, mb + 1>{}, std::integral_constant<int, nxt>{});
+            lgkm_wait<8>(lo[cur][0], lo[cur][1], lo[cur][2], lo[cur][3]);
+            lgkm_wait<8>(hi[cur][0], hi[cur][1], hi[cur][2], hi[cur][3]);
+          } else {
+            lgkm_wait<0>(lo[cur][0], lo[cur][1], lo[cur][2], lo[cur][3]);
+            lgkm_wait<0>(hi[cur][0], hi[cur][1], hi[cur][2], hi[cur][3]);
+          }
+          static_for<4>([&](auto ks_) {
+            constexpr int ks = decltype(ks_)::value;
+            const bf16x8 af = join_tr(lo[cur][ks], hi[cur][ks]);
+            o[mb][0] = mfma32(af, pf[ks][0], o[mb][0]);
+            o[mb][1] = mfma32(af, pf[ks][1], o[mb][1]);
+          });
+        });
+      }
     }
+
+    // ---- denominators: sum the two token halves of either query block through LDS
+    raw_barrier();   // everyone is past its last read of the maxima buffer
+    {
+      const float lh = sum_halves(l);
+      if (g == 0) lds_write_b32(mx_wr, lh);
+    }
+    lgkm_wait<0>();
+    raw_barrier();
+    f32x4 ll = lds_read_f32x4(mx_rd);
+    lgkm_wait<0>(ll);
+    if (FIXED) {
+      // a denominator that is not a moderate finite number: the fixed references did not hold.
+      // Every wavefront reads the same four vectors, so the verdict is the same in all of them.
+      const bool bad = !(ll[0] + ll[2] < 0x1p100f) || !(ll[1] + ll[3] < 0x1p100f);
+      if (__builtin_amdgcn_ballot_w64(bad) != 0) return false;
+    }
+  #pragma unroll
+    for (int q = 0; q < 2; q++) {
+      const int r_local = (qg * 2 + q) * 32 + n;
+      if (r_local >= a.R) continue;
+      const int64_t row = (int64_t)b * a.R + r_local;
+      const float lt = ll[q] + ll[q + 2];
+      float* l_dst = a.lat_lse + (size_t)item * a.rows + row;
+      if (lt > 0.f) {
+        const float inv = 1.f / lt;
+        __bf16* o_dst = a.lat_o + ((size_t)item * a.rows + row) * D_L + 128 * wave + 4 * g;
+  #pragma unroll
+        for (int mb = 0; mb < 4; mb++)
+  #pragma unroll
+          for (int v4 = 0; v4 < 4; v4++) {
+            bf16x4 w;
+  #pragma unroll
+            for (int e = 0; e < 4; e++) w[e] = (__bf16)(o[mb][q][4 * v4 + e] * inv);
+            *(bf16x4*)(o_dst + 32 * mb + 8 * v4) = w;
+          }
+        if (wave == q && g == 0) *l_dst = (m[q] + fast_log2(lt)) * LN2;
+      } else if (wave == q && g == 0) {
+        *l_dst = -INFINITY;   // the causal mask hid every token of this chunk from this query
+      }
+    }
+    return true;
+  };
+  if (args.moving_only) {
+    walk(std::false_type{}, true);
+  } else if (!walk(std::true_type{}, true)) {
+    walk(std::false_type{}, false);
   }
 }
 
@@ -441,6 +476,7 @@ int mfma_absorb64_attention(const Plan& p, const DecodeArgs& d, const AbsorbArgs
   args.nqg = (a.R + 63) / 64;
   args.n_lat = p.n_lat;
   args.B = p.B;
+  args.moving_only = (debug_flags() & 0x800) != 0;
   const long long units = (long long)p.n_lat * p.B;
   const long long wgs = 8LL * args.nqg * ((units + 7) / 8);
   if (wgs > 0x7fffffffLL) return TMLA_ERR_UNSUPPORTED;

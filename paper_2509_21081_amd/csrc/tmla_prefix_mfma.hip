@@ -858,17 +858,6 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_token_split_kernel(PrefixA
     bt = a.block_table + (size_t)mb * a.max_blocks;
   }
 
-  bf16x8 qf[2][12];
-  load_q_frags(a, h, q0, n, g, qf, q_end);
-  // resident before the streamed loads start: no wait on them inside the loop
-#pragma unroll
-  for (int nb = 0; nb < 2; nb++)
-#pragma unroll
-    for (int ks = 0; ks < 12; ks += 4)
-      asm volatile("s_waitcnt vmcnt(0)"
-                   : "+v"(qf[nb][ks]), "+v"(qf[nb][ks + 1]), "+v"(qf[nb][ks + 2]),
-                     "+v"(qf[nb][ks + 3])::"memory");
-
   const int tb0 = sp * a.blocks_per_split;
   const int tb1 = min(PAGED ? (len + TOK_BLK - 1) / TOK_BLK : a.ntb, tb0 + a.blocks_per_split);
   const __bf16* kbase = a.pk + ((size_t)h * a.ntb) * K_BLK_ELEMS + lane * 8;
@@ -905,6 +894,18 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_token_split_kernel(PrefixA
   const int nmine = first < tb1 ? (tb1 - first + 3) / 4 : 0;
   if (nmine > 0) issue(first, 0);
   if (nmine > 1) issue(first + 4, 1);
+  // The queries are requested behind the first two blocks, so their latency runs alongside the
+  // stream's instead of in front of it, and waited for together with those blocks: resident
+  // from here on, no wait on them inside the loop.
+  bf16x8 qf[2][12];
+  load_q_frags(a, h, q0, n, g, qf, q_end);
+#pragma unroll
+  for (int nb = 0; nb < 2; nb++)
+#pragma unroll
+    for (int ks = 0; ks < 12; ks += 4)
+      asm volatile("s_waitcnt vmcnt(0)"
+                   : "+v"(qf[nb][ks]), "+v"(qf[nb][ks + 1]), "+v"(qf[nb][ks + 2]),
+                     "+v"(qf[nb][ks + 3])::"memory");
   for (int j = 0; j < nmine; j++) {
     if (j + 1 < nmine) vm_wait<20>();   // block j has landed, block j+1 may still be in flight
     else vm_wait<0>();

@@ -135,6 +135,35 @@ def test_prefix_scores_far_from_the_first_block(gain, first, gpu_device, monkeyp
         assert np.array_equal(got, alone) and np.array_equal(got_lse, alone_lse)
 
 
+@pytest.mark.parametrize("gain", [256.0, 16.0, 1.0 / 64.0])
+def test_suffix_scores_far_from_the_first_step(gain, gpu_device, monkeypatch):
+    """The same for the absorb pass over the suffix with more than 32 query rows per request: the
+    64-row kernel first walks a chunk with exponent references fixed at its first 64 tokens and
+    walks it again with moving references if its denominators overflowed.  The RoPE part of every
+    cached suffix row behind the first block is scaled (stored as given, so exact for the
+    oracle); one chunk per request (forced), so with gain 256 every workgroup overflows and the
+    result is bit-identical to the walk with moving references alone (debug flag 0x800)."""
+    monkeypatch.setenv("TMLA_SUFFIX_CHUNK", "4096")
+    spec = W.small_spec(name="suffix_growth", dtype="bf16", batch=6, heads=128, q_len=1,
+                        prefix_len=40, suffix_min=200, suffix_max=700, seed=91)
+    wl = W.make_workload(spec)
+    wl.pool[:, :, 512:] *= gain
+    for b in range(spec.batch):
+        wl.pool[int(wl.block_table[b, 0]), :, 512:] /= gain     # the first 64 tokens stay
+    ref, ref_lse = O.mla_decode_definition(**wl.as_float64())
+    print(f"suffix score growth, gain={gain}", flush=True)
+    lg = max(1.0, gain / 4.0)
+    for mode in ["mixed", "absorb_only"]:
+        got, got_lse = Hh.run_library(wl, mode, gpu_device)
+        alone, alone_lse = Hh.run_library(wl, mode, gpu_device, flags=0x800)
+        Hh.assert_parity(got, got_lse, ref, ref_lse, "bf16", f"suffix_growth_{gain}/{mode}",
+                         logit_gain=lg)
+        Hh.assert_parity(alone, alone_lse, ref, ref_lse, "bf16",
+                         f"suffix_growth_{gain}/{mode}/moving", logit_gain=lg)
+        if gain >= 256.0 and mode == "mixed":
+            assert np.array_equal(got, alone) and np.array_equal(got_lse, alone_lse)
+
+
 @pytest.mark.parametrize("flags", [0, 1], ids=["mfma", "scalar"])
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 @pytest.mark.parametrize("ntok", [1, 31, 64, 100, 300])
