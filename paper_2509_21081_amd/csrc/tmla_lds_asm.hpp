@@ -104,6 +104,23 @@ __device__ inline void dma16(const void* src, void* dst) {
   __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(lds_char_ptr)dst, 16, 0, 0);
 }
 
+// The same transfer with the address split into a wave-uniform base (in scalar registers) and a
+// 32-bit per-lane offset: no 64-bit vector additions per transfer.  `lds` + `lds2` = wave-uniform
+// LDS byte address (two terms so that the sum lands in M0 directly).  The statement sets M0 behind the compiler's back, which is safe only in kernels that
+// issue every global-to-LDS transfer through it and use nothing else that reads M0.
+__device__ inline void dma16_scalar_base(uint32_t lane_off, const void* base, uint32_t lds,
+                                         uint32_t lds2 = 0) {
+  // wave-uniform by contract; made explicit so that both live in scalar registers
+  const uint64_t u = (uint64_t)base;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+  base = (const void*)(((uint64_t)hi << 32) | lo);
+  lds = __builtin_amdgcn_readfirstlane(lds);
+  lds2 = __builtin_amdgcn_readfirstlane(lds2);
+  asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               ::"v"(lane_off), "s"(base), "s"(lds), "s"(lds2) : "memory", "scc");
+}
+
 // Scalar (SMEM) load of one int from a wave-uniform address.  A vector load here would have to be
 // waited for with vmcnt(0), draining the tile prefetch; the scalar cache is only read.
 __device__ inline int scalar_load_i32(const int32_t* p) {

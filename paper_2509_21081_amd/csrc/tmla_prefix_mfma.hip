@@ -377,16 +377,6 @@ __device__ inline void pl_mfma_o(f32x16& d, const bf16x8& a, const bf16x8& b) {
 __device__ inline void pl_mfma_drain() {
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");
 }
-// 64 lanes x 16 bytes from `base` (wave-uniform, in scalar registers) + `lane_off` (per lane) to
-// 1 KiB of LDS at the wave-uniform byte address `lds`.  Written out so that the address is the
-// scalar-base form (no 64-bit vector additions per transfer).  The statement sets M0 behind
-// the compiler's back, which is safe only because this kernel issues every global-to-LDS
-// transfer through it and uses nothing else that reads M0.
-__device__ inline void pl_dma16(uint32_t lane_off, const void* base, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               ::"v"(lane_off), "s"(base), "s"(lds) : "memory");
-}
-
 __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int h = blockIdx.x, mb = blockIdx.y, sp = blockIdx.z;
@@ -433,12 +423,12 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
   using NOGUARD = std::false_type;
   auto dma_k = [&](int k, int f, auto guard_tag) __attribute__((always_inline)) {
     if (!decltype(guard_tag)::value || k < nblk)
-      pl_dma16(lane_off[f], kbase + (size_t)k * PL_K_BYTES,
+      dma16_scalar_base(lane_off[f], kbase + (size_t)k * PL_K_BYTES,
                lds_base + (k & (PL_NK - 1)) * PL_K_BYTES + f * 4096);
   };
   auto dma_v = [&](int kv, int f, auto guard_tag) __attribute__((always_inline)) {
     if (!decltype(guard_tag)::value || (kv >= 0 && kv < nblk))
-      pl_dma16(lane_off[f], vbase + (size_t)kv * PL_V_BYTES,
+      dma16_scalar_base(lane_off[f], vbase + (size_t)kv * PL_V_BYTES,
                lds_base + PL_V_BASE + (kv & (PL_NV - 1)) * PL_V_BYTES + f * 4096);
   };
   for (int k = 0; k < PL_AHEAD - 1; k++) {
