@@ -216,8 +216,7 @@ int typhoon_mla_combine_lse(int32_t num_partials, int64_t rows, int32_t width,
  *     is then meaningless unless the workspace still holds the other stages' results.
  *   bit 9 (0x200): scalar kernel for the naive suffix attention of naive_only mode.
  *   bit 10 (0x400): naive prefix attention with more than 128 queries per head runs on the
- *     8-wavefront kernel alone (otherwise it only redoes the workgroups in which the software-
- *     pipelined kernel's fixed exponent references overflowed).
+ *     8-wavefront kernel (moving exponent references) instead of the software-pipelined one.
  *   bit 11 (0x800): the absorb attention kernel for more than 32 query rows per request walks
  *     every chunk with moving exponent references (otherwise only chunks in which its first walk,
  *     with references fixed at the chunk's first tokens, overflowed).

@@ -114,8 +114,6 @@ void layout_workspace(Plan* p) {
   p->off_naive_lse = off; off = align_up(off + (size_t)p->n_naive * p->rows * 4, 256);
   p->off_lat_o = off;     off = align_up(off + (size_t)p->n_lat * p->rows * D_L * esz, 256);
   p->off_lat_lse = off;   off = align_up(off + (size_t)p->n_lat * p->rows * 4, 256);
-  p->off_prefix_redo = off;
-  off = align_up(off + (size_t)4 * p->H * ceil_div(std::max(1, p->B * p->Sq), 256) * std::max(1, p->n_naive), 256);
   p->total = off + 256;
 }
 

@@ -82,7 +82,6 @@ struct Plan {
   int n_naive;         // = np_split + ns_chunks   (128-wide partials per row)
   int n_lat;           // = ap_chunks + as_chunks  (512-wide latent partials per row)
   size_t off_qabs, off_naive_o, off_naive_lse, off_lat_o, off_lat_lse, total;
-  size_t off_prefix_redo;   // one int per workgroup of the naive prefix pass
 };
 
 int debug_flags();   // current typhoon_mla_set_debug_flags value

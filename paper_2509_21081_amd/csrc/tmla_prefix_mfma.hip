@@ -38,9 +38,6 @@ struct PrefixArgs {
   const int32_t* lens;
   int max_blocks, page_shift;   // 32-token blocks per cache page = 1 << page_shift
   int Sq, first_slot;           // partial slot of chunk 0
-  // query-split kernels: one flag per workgroup.  The pipelined kernel sets it when its result
-  // must be recomputed; the 8-wavefront kernel, launched behind it, returns at once where it is 0.
-  int* redo;
 };
 
 __device__ inline void load_q_frags(const PrefixArgs& a, int h, int q0, int n, int g,
@@ -135,7 +132,6 @@ __global__ void __launch_bounds__(512 / NB, 1) prefix_attn_query_split_kernel(Pr
   const int h = blockIdx.x, mb = blockIdx.y, sp = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  if (a.redo && a.redo[blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)] == 0) return;
   const int q0 = mb * QS_QUERIES + wave * (32 * NB);   // first query of this wavefront
 
   const int tb0 = sp * a.blocks_per_split;
@@ -431,30 +427,16 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
       dma16_scalar_base(lane_off[f], vbase + (size_t)kv * PL_V_BYTES,
                lds_base + PL_V_BASE + (kv & (PL_NV - 1)) * PL_V_BYTES + f * 4096);
   };
-  for (int k = 0; k < PL_AHEAD - 1; k++) {
-    dma_k(k, 0, GUARD{}); dma_k(k, 1, GUARD{}); dma_k(k, 2, GUARD{});
-    dma_v(k - 3, 0, GUARD{}); dma_v(k - 3, 1, GUARD{});
-  }
-
   f32x16 o[4][2];
-#pragma unroll
-  for (int db = 0; db < 4; db++)
-#pragma unroll
-    for (int nb = 0; nb < 2; nb++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) o[db][nb][v] = 0.f;
-  // (pins the zeroing here: moved down next to the first MFMA that accumulates into them, the
-  // register writes would sit closer to it than the hardware allows without wait states, which
-  // nobody inserts in front of an MFMA written in assembly)
-  asm volatile("" : "+a"(o[0][0]), "+a"(o[1][0]), "+a"(o[2][0]), "+a"(o[3][0]), "+a"(o[0][1]),
-                    "+a"(o[1][1]), "+a"(o[2][1]), "+a"(o[3][1]));
-  // Softmax bookkeeping.  The exponent reference m of a query is fixed once, to the maximum of
-  // its scores over the first block of this split, and never moved inside the loop: the
-  // result does not depend on the reference (numerator and denominator share it), only the
-  // float range does.  Scores more than ~2^7 (log2 units) above the first block's maximum
-  // would overflow; that shows as a denominator that is not a moderate finite number, is
-  // checked once at the end, and sends the whole workgroup to the fallback kernel.
+  // Softmax bookkeeping.  The exponent reference m of a query is fixed before the walk over the
+  // split and never moved inside the loop: the result does not depend on the reference
+  // (numerator and denominator share it), only the float range does.  The first walk takes the
+  // maximum of the query's scores over the first block; scores more than ~2^7 (log2 units) above
+  // that would overflow, which shows as a denominator that is not a moderate finite number and
+  // is checked once at the end.  Then (rare) the exact maxima over the whole split are formed in
+  // a scores-only pass and the split is walked again with those.
   float m[2] = {0.f, 0.f}, l[2] = {0.f, 0.f};
+  float m_exact[2] = {0.f, 0.f};
   const float c = a.c;
 
   // top of period t: groups t+3 .. t+PL_AHEAD-1 may still be in flight, group t+2 must have
@@ -482,15 +464,6 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
   bf16x8 fr[8];          // fragment ring: fragment j of period t lives in fr[(4 (t & 1) + j) % 8]
   f32x16 sb[2][2];       // scores of blocks of even / odd index
   bf16x8 pb[2][2][2];    // probabilities of blocks of even / odd index
-#pragma unroll
-  for (int i = 0; i < 8; i++)
-#pragma unroll
-    for (int e = 0; e < 8; e++) (&pb[0][0][0])[i][e] = (__bf16)0.f;
-  // (from here on these zeros are values in registers like any other: known to be zero, they
-  // would be re-created right in front of the MFMA that reads them, closer than the hardware
-  // allows without wait states, which nobody inserts in front of an MFMA written in assembly)
-  asm volatile("" : "+v"(pb[0][0][0]), "+v"(pb[0][0][1]), "+v"(pb[0][1][0]), "+v"(pb[0][1][1]),
-                    "+v"(pb[1][0][0]), "+v"(pb[1][0][1]), "+v"(pb[1][1][0]), "+v"(pb[1][1][1]));
 
   // Period t = 0 .. nfull.  The instruction stream is the same for every period; at the two ends
   // some of it runs on data that is not there, arranged to be harmless:
@@ -628,15 +601,24 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
 
   using P0 = std::integral_constant<int, 0>;
   using P1 = std::integral_constant<int, 1>;
-  if (nblk > 0) {
-    // before period 0: the scores of block 0 and from them the exponent references, the first
-    // fragments of K(1), group PL_AHEAD - 1
-    sync(-1, NOGUARD{});
-    {
-      const uint32_t ka0 = lane_addr, ka1 = lane_addr + PL_K_BYTES;
+
+  // Scores-only pass over the split: the exact maximum of every query's scores (rare path, plain
+  // double buffering of K through the ring, one barrier per block).
+  auto exact_maxima = [&]() __attribute__((always_inline)) {
+    float mx[2] = {-INFINITY, -INFINITY};
+    dma_k(0, 0, GUARD{}); dma_k(0, 1, GUARD{}); dma_k(0, 2, GUARD{});
+    for (int bk = 0; bk < nblk; bk++) {
+      if (bk + 1 < nblk) {
+        dma_k(bk + 1, 0, GUARD{}); dma_k(bk + 1, 1, GUARD{}); dma_k(bk + 1, 2, GUARD{});
+        vm_wait<3>();
+      } else {
+        vm_wait<0>();
+      }
+      raw_barrier();
+      const uint32_t ka = lane_addr + (bk & (PL_NK - 1)) * PL_K_BYTES;
       static_for<12>([&](auto j_tag) {
         constexpr int j = decltype(j_tag)::value;
-        fr[j % 8] = lds_read_b128<1024 * j>(ka0);
+        fr[j % 8] = lds_read_b128<1024 * j>(ka);
         lgkm_wait<0>(fr[j % 8]);
         static_for<2>([&](auto nb_tag) {
           constexpr int nb = decltype(nb_tag)::value;
@@ -644,79 +626,140 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
           else pl_mfma_s(sb[0][nb], fr[j % 8], qf[nb][j]);
         });
       });
-      static_for<PL_D>([&](auto j_tag) {
-        constexpr int j = decltype(j_tag)::value;
-        fr[j] = lds_read_b128<1024 * j>(ka1);
-      });
-      const int k = PL_AHEAD - 1;
-      dma_k(k, 0, GUARD{}); dma_k(k, 1, GUARD{}); dma_k(k, 2, GUARD{});
-      dma_v(k - 3, 0, GUARD{}); dma_v(k - 3, 1, GUARD{});
       pl_mfma_drain();
-      const int limit0 = nfull > 0 ? 32 : tail_limit;
-      m[0] = block_max(sb[0][0], limit0);
-      m[1] = block_max(sb[0][1], limit0);
-    }
-    using ST = std::true_type;
-    using GN = std::false_type;
-    period(0, P0{}, GN{});
-    if (1 <= nfull) period(1, P1{}, GN{});
-    int t = 2;
-    for (; t + 1 + PL_AHEAD < nblk; t += 2) {
-      period(t, P0{}, ST{});
-      period(t + 1, P1{}, ST{});
-    }
-    for (; t <= nfull; t += 2) {
-      period(t, P0{}, GN{});
-      if (t + 1 <= nfull) period(t + 1, P1{}, GN{});
-    }
-    lgkm_wait<0>();
-    pl_mfma_drain();
-  }
-  if (has_tail) {
-    // The scores of the partial last block were formed by the loop's last period (or above, if
-    // the block is the only one).  Masked probabilities against the same references, then P V.
-    vm_wait<0>();
-    raw_barrier();
-    auto tail = [&](auto par_tag) __attribute__((always_inline)) {
-      constexpr int PAR = decltype(par_tag)::value;
-      bf16x8 pt[2][2];
+      const int lim = (has_tail && bk == nblk - 1) ? tail_limit : 32;
 #pragma unroll
       for (int nb = 0; nb < 2; nb++)
 #pragma unroll
-        for (int v = 0; v < 16; v++) {
-          const float e = acc_row(v, g) < tail_limit
-                              ? fast_exp2(__builtin_fmaf(sb[PAR][nb][v], c, -m[nb])) : 0.f;
-          l[nb] += e;
-          pt[nb][v / 8][v % 8] = (__bf16)e;
-        }
-      const uint32_t va = lane_addr + PL_V_BASE + ((nblk - 1) & (PL_NV - 1)) * PL_V_BYTES;
-      bf16x8 vf[8];
-      static_for<8>([&](auto j) { vf[j] = lds_read_b128<1024 * decltype(j)::value>(va); });
-      lgkm_wait<0>(vf[0], vf[1], vf[2], vf[3]);
-      lgkm_wait<0>(vf[4], vf[5], vf[6], vf[7]);
-#pragma unroll
-      for (int kk = 0; kk < 2; kk++)
-#pragma unroll
-        for (int db = 0; db < 4; db++)
-#pragma unroll
-          for (int nb = 0; nb < 2; nb++) pl_mfma_o(o[db][nb], vf[kk * 4 + db], pt[nb][kk]);
-      pl_mfma_drain();
-    };
-    if (nfull & 1) tail(P1{});
-    else tail(P0{});
-  }
+        for (int v = 0; v < 16; v++)
+          if (acc_row(v, g) < lim) mx[nb] = fmaxf(mx[nb], sb[0][nb][v]);
+    }
+    m_exact[0] = max_halves(mx[0]) * c;
+    m_exact[1] = max_halves(mx[1]) * c;
+    raw_barrier();   // everybody is done reading before the next walk refills the ring
+  };
 
-  // a denominator that is not a moderate finite number: the fixed references did not hold
-  const bool bad_lane = !(l[0] < 0x1p100f) || !(l[1] < 0x1p100f);
-  const bool bad_wave = __builtin_amdgcn_ballot_w64(bad_lane) != 0;
-  if (a.redo) {
+  for (int attempt = 0;; attempt++) {
+    // (the zeros are pinned: moved down next to the first MFMA that reads them, or re-created
+    // there because they are known to be zero, the register writes would sit closer to that MFMA
+    // than the hardware allows without wait states, which nobody inserts in front of an MFMA
+    // written in assembly)
+#pragma unroll
+    for (int db = 0; db < 4; db++)
+#pragma unroll
+      for (int nb = 0; nb < 2; nb++)
+#pragma unroll
+        for (int v = 0; v < 16; v++) o[db][nb][v] = 0.f;
+    asm volatile("" : "+a"(o[0][0]), "+a"(o[1][0]), "+a"(o[2][0]), "+a"(o[3][0]), "+a"(o[0][1]),
+                      "+a"(o[1][1]), "+a"(o[2][1]), "+a"(o[3][1]));
+#pragma unroll
+    for (int i = 0; i < 8; i++)
+#pragma unroll
+      for (int e = 0; e < 8; e++) (&pb[0][0][0])[i][e] = (__bf16)0.f;
+    asm volatile("" : "+v"(pb[0][0][0]), "+v"(pb[0][0][1]), "+v"(pb[0][1][0]), "+v"(pb[0][1][1]),
+                      "+v"(pb[1][0][0]), "+v"(pb[1][0][1]), "+v"(pb[1][1][0]), "+v"(pb[1][1][1]));
+    l[0] = l[1] = 0.f;
+    for (int k = 0; k < PL_AHEAD - 1; k++) {
+      dma_k(k, 0, GUARD{}); dma_k(k, 1, GUARD{}); dma_k(k, 2, GUARD{});
+      dma_v(k - 3, 0, GUARD{}); dma_v(k - 3, 1, GUARD{});
+    }
+
+    if (nblk > 0) {
+      // before period 0: the scores of block 0 and from them the exponent references, the first
+      // fragments of K(1), group PL_AHEAD - 1
+      sync(-1, NOGUARD{});
+      {
+        const uint32_t ka0 = lane_addr, ka1 = lane_addr + PL_K_BYTES;
+        static_for<12>([&](auto j_tag) {
+          constexpr int j = decltype(j_tag)::value;
+          fr[j % 8] = lds_read_b128<1024 * j>(ka0);
+          lgkm_wait<0>(fr[j % 8]);
+          static_for<2>([&](auto nb_tag) {
+            constexpr int nb = decltype(nb_tag)::value;
+            if constexpr (j == 0) pl_mfma_s_first(sb[0][nb], fr[j % 8], qf[nb][j]);
+            else pl_mfma_s(sb[0][nb], fr[j % 8], qf[nb][j]);
+          });
+        });
+        static_for<PL_D>([&](auto j_tag) {
+          constexpr int j = decltype(j_tag)::value;
+          fr[j] = lds_read_b128<1024 * j>(ka1);
+        });
+        const int k = PL_AHEAD - 1;
+        dma_k(k, 0, GUARD{}); dma_k(k, 1, GUARD{}); dma_k(k, 2, GUARD{});
+        dma_v(k - 3, 0, GUARD{}); dma_v(k - 3, 1, GUARD{});
+        pl_mfma_drain();
+        if (attempt == 0) {
+          const int limit0 = nfull > 0 ? 32 : tail_limit;
+          m[0] = block_max(sb[0][0], limit0);
+          m[1] = block_max(sb[0][1], limit0);
+        } else {
+          m[0] = m_exact[0];
+          m[1] = m_exact[1];
+        }
+      }
+      using ST = std::true_type;
+      using GN = std::false_type;
+      period(0, P0{}, GN{});
+      if (1 <= nfull) period(1, P1{}, GN{});
+      int t = 2;
+      for (; t + 1 + PL_AHEAD < nblk; t += 2) {
+        period(t, P0{}, ST{});
+        period(t + 1, P1{}, ST{});
+      }
+      for (; t <= nfull; t += 2) {
+        period(t, P0{}, GN{});
+        if (t + 1 <= nfull) period(t + 1, P1{}, GN{});
+      }
+      lgkm_wait<0>();
+      pl_mfma_drain();
+    }
+    if (has_tail) {
+      // The scores of the partial last block were formed by the loop's last period (or above, if
+      // the block is the only one).  Masked probabilities against the same references, then P V.
+      vm_wait<0>();
+      raw_barrier();
+      auto tail = [&](auto par_tag) __attribute__((always_inline)) {
+        constexpr int PAR = decltype(par_tag)::value;
+        bf16x8 pt[2][2];
+  #pragma unroll
+        for (int nb = 0; nb < 2; nb++)
+  #pragma unroll
+          for (int v = 0; v < 16; v++) {
+            const float e = acc_row(v, g) < tail_limit
+                                ? fast_exp2(__builtin_fmaf(sb[PAR][nb][v], c, -m[nb])) : 0.f;
+            l[nb] += e;
+            pt[nb][v / 8][v % 8] = (__bf16)e;
+          }
+        const uint32_t va = lane_addr + PL_V_BASE + ((nblk - 1) & (PL_NV - 1)) * PL_V_BYTES;
+        bf16x8 vf[8];
+        static_for<8>([&](auto j) { vf[j] = lds_read_b128<1024 * decltype(j)::value>(va); });
+        lgkm_wait<0>(vf[0], vf[1], vf[2], vf[3]);
+        lgkm_wait<0>(vf[4], vf[5], vf[6], vf[7]);
+  #pragma unroll
+        for (int kk = 0; kk < 2; kk++)
+  #pragma unroll
+          for (int db = 0; db < 4; db++)
+  #pragma unroll
+            for (int nb = 0; nb < 2; nb++) pl_mfma_o(o[db][nb], vf[kk * 4 + db], pt[nb][kk]);
+        pl_mfma_drain();
+      };
+      if (nfull & 1) tail(P1{});
+      else tail(P0{});
+    }
+
+
+    if (attempt == 1) break;
+    // a denominator that is not a moderate finite number: the references did not hold
+    const bool bad_lane = !(l[0] < 0x1p100f) || !(l[1] < 0x1p100f);
+    const bool bad_wave = __builtin_amdgcn_ballot_w64(bad_lane) != 0;
     int* flags = (int*)smem;
     __syncthreads();   // every transfer has landed and every ring read is done
     if (lane == 0) flags[wave] = bad_wave ? 1 : 0;
     __syncthreads();
-    if (tid == 0)
-      a.redo[blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)] =
-          flags[0] | flags[1] | flags[2] | flags[3];
+    const int bad_wg = flags[0] | flags[1] | flags[2] | flags[3];
+    __syncthreads();   // the flags are read before the ring is written again
+    if (__builtin_amdgcn_readfirstlane(bad_wg) == 0) break;
+    exact_maxima();
   }
 
 #pragma unroll
@@ -1011,13 +1054,8 @@ int mfma_prefix_attention(const Plan& p, const DecodeArgs& d) {
         return TMLA_ERR_HIP;
       pl_attr = true;
     }
-    // The pipelined kernel first; the 8-wavefront kernel (which moves its exponent references
-    // as it goes) behind it on the same grid, doing work only where the first one gave up.
     dim3 grid(p.H, (a.M + PL_QUERIES - 1) / PL_QUERIES, p.np_split);
-    a.redo = (int*)(d.ws + p.off_prefix_redo);
     hipLaunchKernelGGL(prefix_attn_pipelined_kernel, grid, dim3(256), PL_LDS_BYTES, d.stream, a);
-    hipLaunchKernelGGL(prefix_attn_query_split_kernel<1>, grid, dim3(512), QS_LDS_BYTES, d.stream,
-                       a);
   } else if (a.M > 128) {
     dim3 grid(p.H, (a.M + QS_QUERIES - 1) / QS_QUERIES, p.np_split);
     // NB = 1 measured faster than NB = 2 on every configuration: vector-ALU and matrix-core

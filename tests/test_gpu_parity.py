@@ -114,8 +114,9 @@ def test_prefix_scores_far_from_the_first_block(gain, first, gpu_device, monkeyp
     that part of a key is stored as given, so the oracle sees exactly what the kernels see): the
     scores there lie far above (or below) those of the first block, whose maximum the pipelined
     kernel takes as its exponent reference.  With gain 256 its denominators overflow for every
-    query: it must notice, and the 8-wavefront kernel behind it must redo every workgroup,
-    which makes the result bit-identical to that kernel running alone (debug flag 0x400)."""
+    query: it must notice, form the exact maxima in a scores-only pass and walk the prefix
+    again.  The 8-wavefront kernel (moving references; debug flag 0x400) is held against the
+    oracle on the same inputs."""
     monkeypatch.setenv("TMLA_PREFIX_SPLITS", "1")
     spec = W.small_spec(name="growth", dtype="bf16", batch=150, heads=16, q_len=1,
                         prefix_len=1100, suffix_min=0, suffix_max=30, seed=77)
@@ -131,8 +132,6 @@ def test_prefix_scores_far_from_the_first_block(gain, first, gpu_device, monkeyp
     Hh.assert_parity(got, got_lse, ref, ref_lse, "bf16", f"growth_{gain}_{first}", logit_gain=lg)
     Hh.assert_parity(alone, alone_lse, ref, ref_lse, "bf16", f"growth_{gain}_{first}/8-wave",
                      logit_gain=lg)
-    if gain >= 256.0:
-        assert np.array_equal(got, alone) and np.array_equal(got_lse, alone_lse)
 
 
 @pytest.mark.parametrize("gain", [256.0, 16.0, 1.0 / 64.0])
