@@ -118,15 +118,9 @@ __device__ inline float softmax_block_fast(f32x16& s, float& m, float& l, float 
     q0[v] = (__bf16)fast_exp2(__builtin_fmaf(s[v], c, -m));       // m = -inf gives inf: falls through
     q1[v] = (__bf16)fast_exp2(__builtin_fmaf(s[8 + v], c, -m));
   }
-  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
   float sum = 0.f;
 #pragma unroll
-  for (int v = 0; v < 8; v += 2) {
-    const bf16x2 a = {q0[v], q0[v + 1]};
-    const bf16x2 b = {q1[v], q1[v + 1]};
-    sum = __builtin_amdgcn_fdot2_f32_bf16(a, ones, sum, false);
-    sum = __builtin_amdgcn_fdot2_f32_bf16(b, ones, sum, false);
-  }
+  for (int v = 0; v < 8; v++) sum += (float)q0[v] + (float)q1[v];
   const bool good = sum <= 16.f * 256.f;   // 2^(RESCALE_TAU + 4); false for inf and NaN
   if (__builtin_amdgcn_ballot_w64(!good) == 0) {
     l += sum;

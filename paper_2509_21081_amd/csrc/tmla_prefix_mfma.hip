@@ -369,6 +369,22 @@ __device__ inline void pl_mfma_s(f32x16& d, const bf16x8& a, const bf16x8& b) {
 __device__ inline void pl_mfma_o(f32x16& d, const bf16x8& a, const bf16x8& b) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b));
 }
+// the same, behind a wait for the oldest outstanding fragment read (operand a)
+__device__ inline void pl_mfma_s_first_w(f32x16& d, const bf16x8& a, const bf16x8& b) {
+  asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0"
+               : "=&v"(d) : "v"(a), "a"(b), "n"(PL_D - 1));
+}
+__device__ inline void pl_mfma_s_w(f32x16& d, const bf16x8& a, const bf16x8& b) {
+  asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
+               : "+v"(d) : "v"(a), "a"(b), "n"(PL_D - 1));
+}
+__device__ inline void pl_mfma_o_w(f32x16& d, const bf16x8& a, const bf16x8& b) {
+  asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
+               : "+a"(d) : "v"(a), "v"(b), "n"(PL_D - 1));
+}
+__device__ inline void pl_mfma_l(f32x16& d, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b));
+}
 // enough idle issue slots for the last MFMA (16 passes) to have written its result
 __device__ inline void pl_mfma_drain() {
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");
@@ -435,7 +451,7 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
   // that would overflow, which shows as a denominator that is not a moderate finite number and
   // is checked once at the end.  Then (rare) the exact maxima over the whole split are formed in
   // a scores-only pass and the split is walked again with those.
-  float m[2] = {0.f, 0.f}, l[2] = {0.f, 0.f};
+  float m[2] = {0.f, 0.f}, l[2] = {0.f, 0.f}, lt[2] = {0.f, 0.f};
   float m_exact[2] = {0.f, 0.f};
   const float c = a.c;
 
@@ -462,6 +478,14 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
   };
 
   bf16x8 fr[8];          // fragment ring: fragment j of period t lives in fr[(4 (t & 1) + j) % 8]
+  // Denominators: every row of lacc[nb] holds, for this lane's query, the sum of the packed
+  // probabilities over all full blocks (a 32 x 16 matrix of ones times P^T); l[] only collects
+  // the partial last block.
+  f32x16 lacc[2];
+  bf16x8 ones8;
+#pragma unroll
+  for (int e = 0; e < 8; e++) ones8[e] = (__bf16)1.f;
+  asm volatile("" : "+v"(ones8));
   f32x16 sb[2][2];       // scores of blocks of even / odd index
   bf16x8 pb[2][2][2];    // probabilities of blocks of even / odd index
 
@@ -490,55 +514,39 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
     const int kg = t + PL_AHEAD;      // group issued in this period
 
     float xa = 0.f, xb = 0.f, ea = 0.f, eb = 0.f;
-    float sum[2] = {0.f, 0.f};
     // The softmax of block t, two scores (one packed pair of probabilities) per quantum, spread
     // so that no instruction waits for the one before it and no transcendental directly follows
     // an MFMA (either would cost idle issue slots):
-    //   behind the first MFMA of quantum j : arguments of pair j; pack the pair of quantum j-1
-    //   behind the second MFMA             : sum += e_a(j-1); e_a = exp2; sum += e_b(j-1); e_b = exp2
+    //   behind the first MFMA of quantum j : arguments of pair j
+    //   behind the second MFMA             : pack the pair of quantum j-1; e_a(j), e_b(j) = exp2
     // Pair k = elements 2 (k % 8), 2 (k % 8) + 1 of column block k / 8.  The empty statements pin
     // every piece where it is written (the results are only used much later, and would
-    // otherwise be moved down there).
+    // otherwise be moved down there).  The denominators are not summed here: the matrix core
+    // adds the packed probabilities up one period later (see pl_mfma_l below), which costs four
+    // MFMA issue slots per period instead of 32 additions.
     auto part1 = [&](auto j_tag) __attribute__((always_inline)) {
       constexpr int j = decltype(j_tag)::value;
-      float xa_new = 0.f, xb_new = 0.f;
       if constexpr (j < 16) {
         constexpr int nb = j / 8, v0 = 2 * (j % 8);
-        xa_new = __builtin_fmaf(s_in[nb][v0], c, -m[nb]);
-        xb_new = __builtin_fmaf(s_in[nb][v0 + 1], c, -m[nb]);
-        asm volatile("" : "+v"(xa_new), "+v"(xb_new));
-        PL_SB();
+        xa = __builtin_fmaf(s_in[nb][v0], c, -m[nb]);
+        xb = __builtin_fmaf(s_in[nb][v0 + 1], c, -m[nb]);
+        asm volatile("" : "+v"(xa), "+v"(xb));
       }
+    };
+    auto part2 = [&](auto j_tag) __attribute__((always_inline)) {
+      constexpr int j = decltype(j_tag)::value;
       if constexpr (j >= 1 && j <= 16) {
         constexpr int nb = (j - 1) / 8, v0 = 2 * ((j - 1) % 8);
         const bf16x2 pk = {(__bf16)ea, (__bf16)eb};
         p_out[nb][v0 / 8][v0 % 8] = pk[0];
         p_out[nb][v0 / 8][v0 % 8 + 1] = pk[1];
         asm volatile("" : "+v"(p_out[nb][v0 / 8]));
-      }
-      xa = xa_new;
-      xb = xb_new;
-    };
-    auto part2 = [&](auto j_tag) __attribute__((always_inline)) {
-      constexpr int j = decltype(j_tag)::value;
-      constexpr bool prev = j >= 1 && j <= 16, cur = j < 16;
-      constexpr int nbp = prev ? (j - 1) / 8 : 0;
-      if constexpr (prev) {
-        sum[nbp] += ea;
-        asm volatile("" : "+v"(sum[nbp]));
         PL_SB();
       }
-      if constexpr (cur) {
+      if constexpr (j < 16) {
         ea = fast_exp2(xa);
         asm volatile("" : "+v"(ea));
         PL_SB();
-      }
-      if constexpr (prev) {
-        sum[nbp] += eb;
-        asm volatile("" : "+v"(sum[nbp]));
-        PL_SB();
-      }
-      if constexpr (cur) {
         eb = fast_exp2(xb);
         asm volatile("" : "+v"(eb));
       }
@@ -549,45 +557,54 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
       else dma_v(kg - 3, i - 3, std::integral_constant<bool, !STEADY>{});
     };
 
+    // Quantum j: two MFMAs on fragment j (one per column block of queries).  A wavefront issues
+    // in order and the matrix core takes one MFMA per ~32 cycles, so whatever stands between two
+    // MFMAs beyond ~24 cycles of issue time leaves the matrix core idle: the other work is dealt
+    // out evenly -- behind the first MFMA the two score arguments and the request for fragment
+    // j + PL_D, behind the second the pack and the two exponentials; the transfers and the
+    // denominator MFMAs go to the last quanta, which carry no softmax work.
     static_for<20>([&](auto j_tag) {
       constexpr int j = decltype(j_tag)::value;
       constexpr int cur = (4 * PAR + j) % 8;
-      if constexpr ((j & 1) == 0) {
-        // fragments j + PL_D and j + PL_D + 1 are requested, fragments j and j + 1 awaited
-        static_for<2>([&](auto i_tag) {
-          constexpr int jn = j + PL_D + decltype(i_tag)::value;
+      static_for<2>([&](auto nb_tag) {
+        constexpr int nb = decltype(nb_tag)::value;
+        // (the first MFMA waits for fragment j: PL_D - 1 younger requests may be in flight)
+        if constexpr (j == 0) {
+          if constexpr (nb == 0) pl_mfma_s_first_w(s_out[nb], fr[cur], qf[nb][j]);
+          else pl_mfma_s_first(s_out[nb], fr[cur], qf[nb][j]);
+        } else if constexpr (j < 12) {
+          if constexpr (nb == 0) pl_mfma_s_w(s_out[nb], fr[cur], qf[nb][j]);
+          else pl_mfma_s(s_out[nb], fr[cur], qf[nb][j]);
+        } else {
+          constexpr int kk = (j - 12) / 4, db = (j - 12) % 4;
+          if constexpr (nb == 0) pl_mfma_o_w(o[db][nb], fr[cur], p_in[nb][kk]);
+          else pl_mfma_o(o[db][nb], fr[cur], p_in[nb][kk]);
+        }
+        PL_SB();
+        if constexpr (nb == 0) {
+          part1(j_tag);
+          constexpr int jn = j + PL_D;
           constexpr int nxt = (4 * PAR + jn) % 8;
           if constexpr (jn < 12) fr[nxt] = lds_read_b128<1024 * jn>(ka1);
           else if constexpr (jn < 20) fr[nxt] = lds_read_b128<1024 * (jn - 12)>(va);
           else fr[nxt] = lds_read_b128<1024 * (jn - 20)>(ka2);
-        });
-        lgkm_wait<PL_D>(fr[cur], fr[(cur + 1) % 8]);
-      }
-      PL_SB();
-      static_for<2>([&](auto nb_tag) {
-        constexpr int nb = decltype(nb_tag)::value;
-        if constexpr (j == 0) {
-          pl_mfma_s_first(s_out[nb], fr[cur], qf[nb][j]);
-        } else if constexpr (j < 12) {
-          pl_mfma_s(s_out[nb], fr[cur], qf[nb][j]);
         } else {
-          constexpr int kk = (j - 12) / 4, db = (j - 12) % 4;
-          pl_mfma_o(o[db][nb], fr[cur], p_in[nb][kk]);
+          part2(j_tag);
         }
-        PL_SB();
-        if constexpr (nb == 0) part1(j_tag);
-        else part2(j_tag);
-        if constexpr (j % 4 == 0 && nb == 0) dma(std::integral_constant<int, j / 4>{});
+        constexpr int d = 2 * (j - 16) + nb;   // transfer 0..4 of the group
+        if constexpr (d >= 0 && d < 5) dma(std::integral_constant<int, (d >= 0 && d < 5) ? d : 0>{});
         PL_SB();
       });
+      if constexpr (j >= 16) {
+        // denominators of block t-1: ones (32 x 16) times P^T (16 tokens x 32 queries)
+        constexpr int nb = (j - 16) / 2, kk = (j - 16) % 2;
+        pl_mfma_l(lacc[nb], ones8, p_in[nb][kk]);
+        PL_SB();
+      }
     });
     // Control flow joins below and at the top of the next period, and register copies may be
     // placed there; the last MFMAs must have written their results before any such copy.
     pl_mfma_drain();
-    if (STEADY || t < nfull) {
-      l[0] += sum[0];
-      l[1] += sum[1];
-    }
   };
 
   // maximum of this lane's query over the first `limit` tokens of a block of scores, scaled
@@ -658,6 +675,11 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
       for (int e = 0; e < 8; e++) (&pb[0][0][0])[i][e] = (__bf16)0.f;
     asm volatile("" : "+v"(pb[0][0][0]), "+v"(pb[0][0][1]), "+v"(pb[0][1][0]), "+v"(pb[0][1][1]),
                       "+v"(pb[1][0][0]), "+v"(pb[1][0][1]), "+v"(pb[1][1][0]), "+v"(pb[1][1][1]));
+#pragma unroll
+    for (int nb = 0; nb < 2; nb++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) lacc[nb][v] = 0.f;
+    asm volatile("" : "+v"(lacc[0]), "+v"(lacc[1]));
     l[0] = l[1] = 0.f;
     for (int k = 0; k < PL_AHEAD - 1; k++) {
       dma_k(k, 0, GUARD{}); dma_k(k, 1, GUARD{}); dma_k(k, 2, GUARD{});
@@ -730,6 +752,8 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
             l[nb] += e;
             pt[nb][v / 8][v % 8] = (__bf16)e;
           }
+        // packed before the fragment reads, i.e. well in front of the MFMAs that read them
+        asm volatile("s_nop 3" : "+v"(pt[0][0]), "+v"(pt[0][1]), "+v"(pt[1][0]), "+v"(pt[1][1]));
         const uint32_t va = lane_addr + PL_V_BASE + ((nblk - 1) & (PL_NV - 1)) * PL_V_BYTES;
         bf16x8 vf[8];
         static_for<8>([&](auto j) { vf[j] = lds_read_b128<1024 * decltype(j)::value>(va); });
@@ -748,9 +772,11 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
     }
 
 
+    lt[0] = lacc[0][0] + sum_halves(l[0]);
+    lt[1] = lacc[1][0] + sum_halves(l[1]);
     if (attempt == 1) break;
     // a denominator that is not a moderate finite number: the references did not hold
-    const bool bad_lane = !(l[0] < 0x1p100f) || !(l[1] < 0x1p100f);
+    const bool bad_lane = !(lt[0] < 0x1p100f) || !(lt[1] < 0x1p100f);
     const bool bad_wave = __builtin_amdgcn_ballot_w64(bad_lane) != 0;
     int* flags = (int*)smem;
     __syncthreads();   // every transfer has landed and every ring read is done
@@ -765,11 +791,10 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
 #pragma unroll
   for (int nb = 0; nb < 2; nb++) {
     const int qi = q0 + nb * 32 + n;
-    const float lt = sum_halves(l[nb]);
     if (qi >= a.M) continue;
     const size_t row = (size_t)sp * a.rows + (size_t)qi * a.H + h;
-    if (lt > 0.f) {
-      const float inv = 1.f / lt;
+    if (lt[nb] > 0.f) {
+      const float inv = 1.f / lt[nb];
 #pragma unroll
       for (int db = 0; db < 4; db++)
 #pragma unroll
@@ -778,7 +803,7 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
                                  o[db][nb][4 * v4 + 2] * inv, o[db][nb][4 * v4 + 3] * inv);
           *(float4*)(a.o + row * D_V + 32 * db + 8 * v4 + 4 * g) = w;
         }
-      if (g == 0) a.lse[row] = (m[nb] + fast_log2(lt)) * LN2;
+      if (g == 0) a.lse[row] = (m[nb] + fast_log2(lt[nb])) * LN2;
     } else if (g == 0) {
       a.lse[row] = -INFINITY;
     }
