@@ -8,9 +8,13 @@
 //   outputs  O^T += C_N^T P^T: wavefront w takes latent columns [128 w, 128 w + 128) for all 64
 //            queries and all 64 tokens, so each transposed cache fragment read from LDS feeds
 //            two MFMAs (one per query block): 32 MFMAs for 32 transposing reads.
-// LDS bandwidth, not the matrix cores, bounds this kernel (a 32x32x16 MFMA consumes one 1 KiB
-// operand fragment every 32 cycles per SIMD, which is all the LDS can deliver), hence the care
-// to read each fragment once.
+// The LDS, not the matrix cores, bounds this kernel.  Cycle stamps per step (64 rows x 64 tokens,
+// 68 MFMAs per wavefront): score product ~1000 cycles (one 1 KiB fragment per MFMA), exponentials
+// and hand-over ~900, output product ~1350, barriers ~400 -- and the 72 global-to-LDS transfers of
+// the next step's tiles add ~1900 more wherever in the step they are issued (spread over the
+// score MFMAs, taken in turns by the wavefronts, or all inside the exponentials phase): a
+// transfer occupies the LDS for ~26 cycles per KiB while the fragment reads wait.  Hence the care
+// to read each fragment once and the conflict-free tile layout.
 //
 // One step:
 //   barrier A   the step's two tiles have landed; everyone is done with the previous step
@@ -34,10 +38,12 @@
 namespace tmla {
 
 constexpr int A64_P_BYTES = 4 * 2048;                      // probability fragments [wave][kk][lane]
-constexpr int A64_MAX_BYTES = 32 * 16;                     // row maxima [query n][wave]
-constexpr int A64_P_OFF = AB_NSLOT * AB_TILE_BYTES;        // 151552
-constexpr int A64_MAX_OFF = A64_P_OFF + A64_P_BYTES;       // 159744
-constexpr int A64_LDS_BYTES = A64_MAX_OFF + A64_MAX_BYTES; // 160256 <= 160 KiB
+constexpr int A64_P_OFF = AB_NSLOT * AB_TILE_BYTES;        // 155648
+constexpr int A64_LDS_BYTES = A64_P_OFF + A64_P_BYTES;     // 163840 = all of LDS
+// row maxima [query n][wave]: 16 bytes behind the chunks of row n of ring slot 0, which no
+// transfer writes
+constexpr int A64_MAX_OFF = 1024;
+static_assert(AB_ROW_BYTES >= A64_MAX_OFF + 16 && A64_LDS_BYTES <= 163840, "LDS layout");
 
 struct Absorb64Args {
   AbsorbArgs a;
@@ -100,12 +106,7 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
     bt_cache = (lane < nblk_chunk) ? bt[first_blk + lane] : 0;
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(bt_cache)::"memory");
   }
-  DmaLane dl;
-  dl.wave = wave;
-  dl.off0 = lane << 4;
-  dl.off1 = (lane ^ 1) << 4;
-  dl.rope_row = 8 * wave + (lane >> 3);
-  dl.rope_ch = ((lane & 7) ^ ((lane >> 3) & 7)) << 4;
+  const DmaLane dl = dma_lane(wave, lane);
   // The two tiles (32 tokens each) of step `step`, tokens t0 + 64 * step ...  Suffix chunks start
   // on a 64-token boundary and cache blocks hold a multiple of 64 tokens, so one block-table
   // entry serves a step.  A second tile past the end of the chunk is filled with the chunk's
@@ -137,20 +138,12 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
 
   // per-lane LDS byte offsets inside a tile (layout in tmla_absorb_tile.hpp)
   const uint32_t smem_base = lds_addr(smem);
-  const uint32_t s_off = n * AB_ROW_BYTES + ((g ^ ((n >> 2) & 1)) << 4);
-  uint32_t r_off[4];
-#pragma unroll
-  for (int k = 0; k < 4; k++) r_off[k] = AB_MAIN_BYTES + n * 128 + (((2 * k + g) ^ (n & 7)) << 4);
-  //   transposing read for the output product (16-lane groups j = lane/16, r = lane%16):
-  //     token row 16*kk + 8*half + 4*g + r/4, latent 128*wave + 32*mb + 16*(j%2) + 4*(r%4)
-  const int j16 = lane >> 4, r16 = lane & 15;
-  const uint32_t v_off = (4 * g + (r16 >> 2)) * AB_ROW_BYTES +
-                         ((2 * (j16 & 1) + (((r16 & 3) >> 1) ^ g)) << 4) + 8 * (r16 & 1) +
-                         256 * wave;
+  const TileLane tl = tile_lane(lane);
+  const uint32_t v_lo = tl.v_lo + 256 * wave, v_hi = tl.v_hi + 256 * wave;   // own latent quarter
   const uint32_t p_wr = smem_base + A64_P_OFF + wave * 2048 + lane * 16;
   const uint32_t p_rd = smem_base + A64_P_OFF + lane * 16;
-  const uint32_t mx_wr = smem_base + A64_MAX_OFF + n * 16 + wave * 4;
-  const uint32_t mx_rd = smem_base + A64_MAX_OFF + n * 16;
+  const uint32_t mx_rd = smem_base + n * AB_ROW_BYTES + A64_MAX_OFF;
+  const uint32_t mx_wr = mx_rd + wave * 4;
 
   // ---- absorbed query fragments of the own query block (B operand of the score product),
   // staged like cache tiles in slots 2 and 3 while step 0 streams into slots 0 and 1
@@ -184,10 +177,10 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
   {
     const uint32_t qa = smem_base + (2 + qb) * AB_TILE_BYTES;
     static_for<32>([&](auto ks) {
-      qf[decltype(ks)::value] = lds_read_b128<32 * decltype(ks)::value>(qa + s_off);
+      qf[decltype(ks)::value] = tile_score_frag<decltype(ks)::value>(qa, tl);
     });
     static_for<4>([&](auto k) {
-      qf[32 + decltype(k)::value] = lds_read_b128<0>(qa + r_off[decltype(k)::value]);
+      qf[32 + decltype(k)::value] = lds_read_b128<0>(qa + tl.r_off[decltype(k)::value]);
     });
 #pragma unroll
     for (int ks = 0; ks < 36; ks += 4)
@@ -227,7 +220,6 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
 
       // ---- scores: own token half, own query block
       const uint32_t tbase = sbase + th * AB_TILE_BYTES;
-      const uint32_t sa = tbase + s_off;
       f32x16 sacc;
   #pragma unroll
       for (int v = 0; v < 16; v++) sacc[v] = 0.f;
@@ -240,11 +232,11 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
           constexpr int D = decltype(dsel)::value;
           if constexpr (G < 8) {
             static_for<4>([&](auto j) {
-              f[D][j] = lds_read_b128<32 * (4 * G + decltype(j)::value)>(sa);
+              f[D][j] = tile_score_frag<4 * G + decltype(j)::value>(tbase, tl);
             });
           } else {
             static_for<4>([&](auto j) {
-              f[D][j] = lds_read_b128<0>(tbase + r_off[decltype(j)::value]);
+              f[D][j] = lds_read_b128<0>(tbase + tl.r_off[decltype(j)::value]);
             });
           }
         };
@@ -360,7 +352,7 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
       }
       // the first group of transposed cache fragments does not depend on the probabilities: it is
       // requested before barrier C (the probability writes were issued earlier and complete first)
-      const uint32_t va = sbase + v_off;
+      const uint32_t va = sbase + v_lo, vh = sbase + v_hi;
       short4v lo[2][4], hi[2][4];
       auto rdv = [&](auto grp_, auto buf_) __attribute__((always_inline)) {
         constexpr int G = decltype(grp_)::value;   // = mb
@@ -370,7 +362,7 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
           constexpr int thp = ks >> 1, kk = ks & 1;
           constexpr int off = thp * AB_TILE_BYTES + (16 * kk) * AB_ROW_BYTES + 64 * G;
           lo[D][ks] = lds_read_tr16_b64<off>(va);
-          hi[D][ks] = lds_read_tr16_b64<off + 8 * AB_ROW_BYTES>(va);
+          hi[D][ks] = lds_read_tr16_b64<off>(vh);
         });
       };
       rdv(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});

@@ -71,12 +71,7 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
     bt_cache = (lane < nblk_chunk) ? bt[first_blk + lane] : 0;
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(bt_cache)::"memory");
   }
-  DmaLane dl;
-  dl.wave = wave;
-  dl.off0 = lane << 4;
-  dl.off1 = (lane ^ 1) << 4;
-  dl.rope_row = 8 * wave + (lane >> 3);
-  dl.rope_ch = ((lane & 7) ^ ((lane >> 3) & 7)) << 4;
+  const DmaLane dl = dma_lane(wave, lane);
   auto tile_src = [&](int tile) __attribute__((always_inline)) {
     RowSrc s;
     const int tok0 = t0 + tile * 32;
@@ -100,21 +95,10 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
     return smem + (tile % AB_NSLOT) * AB_TILE_BYTES;
   };
 
-  // per-lane LDS byte offsets inside a tile
-  //   score product, latent k-steps ks < 32: row n, chunk 2*ks + g
-  //       -> n*1056 + ((g ^ sw_n) * 16) + 32*ks            (sw_n = (n >> 2) & 1)
-  //   rope k-steps ks = 32 + k: row n, chunk c = 2*k + g in slot c ^ (n & 7)
+  // per-lane LDS byte offsets inside a tile (tmla_absorb_tile.hpp)
   const uint32_t smem_base = lds_addr(smem);
-  const uint32_t s_off = n * AB_ROW_BYTES + ((g ^ ((n >> 2) & 1)) << 4);
-  uint32_t r_off[4];
-#pragma unroll
-  for (int k = 0; k < 4; k++) r_off[k] = AB_MAIN_BYTES + n * 128 + (((2 * k + g) ^ (n & 7)) << 4);
-  //   P V product (transposing read, 16-lane groups j = lane/16, r = lane%16):
-  //     token row 16*kk + 8*half + 4*g + r/4, latent 32*mb + 16*(j%2) + 4*(r%4)
-  const int j16 = lane >> 4, r16 = lane & 15;
-  const uint32_t v_off = (4 * g + (r16 >> 2)) * AB_ROW_BYTES +
-                         ((2 * (j16 & 1) + (((r16 & 3) >> 1) ^ g)) << 4) + 8 * (r16 & 1) +
-                         64 * (lp * MBW);
+  const TileLane tl = tile_lane(lane);
+  const uint32_t v_lo = tl.v_lo + 64 * (lp * MBW), v_hi = tl.v_hi + 64 * (lp * MBW);
 
   // ---- absorbed query fragments (B operand): 36 k-steps of 16.
   // The NQB blocks of 32 absorbed-query rows are staged like cache tiles (same transfers, same
@@ -154,8 +138,8 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
   bf16x8 qf[36];
   {
     const uint32_t qa = smem_base + (NPRE + qb) * AB_TILE_BYTES;
-    static_for<32>([&](auto ks) { qf[decltype(ks)::value] = lds_read_b128<32 * decltype(ks)::value>(qa + s_off); });
-    static_for<4>([&](auto k) { qf[32 + decltype(k)::value] = lds_read_b128<0>(qa + r_off[decltype(k)::value]); });
+    static_for<32>([&](auto ks) { qf[decltype(ks)::value] = tile_score_frag<decltype(ks)::value>(qa, tl); });
+    static_for<4>([&](auto k) { qf[32 + decltype(k)::value] = lds_read_b128<0>(qa + tl.r_off[decltype(k)::value]); });
 #pragma unroll
     for (int ks = 0; ks < 36; ks += 4)
       lgkm_wait<0>(qf[ks], qf[ks + 1], qf[ks + 2], qf[ks + 3]);
@@ -195,7 +179,6 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
     char* pf_dst = slot_ptr(pf);
 
     const uint32_t tbase = smem_base + (tile % AB_NSLOT) * AB_TILE_BYTES;
-    const uint32_t sa = tbase + s_off;
     f32x16 sacc;
 #pragma unroll
     for (int v = 0; v < 16; v++) sacc[v] = 0.f;
@@ -208,11 +191,11 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
         constexpr int D = decltype(dsel)::value;
         if constexpr (G < 8) {
           static_for<4>([&](auto j) {
-            f[D][j] = lds_read_b128<32 * (4 * G + decltype(j)::value)>(sa);
+            f[D][j] = tile_score_frag<4 * G + decltype(j)::value>(tbase, tl);
           });
         } else {
           static_for<4>([&](auto j) {
-            f[D][j] = lds_read_b128<0>(tbase + r_off[decltype(j)::value]);
+            f[D][j] = lds_read_b128<0>(tbase + tl.r_off[decltype(j)::value]);
           });
         }
       };
@@ -251,14 +234,14 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
     }
     {
       // step st = 2*mb + kk; groups of 4 steps (8 transposing reads), double buffered
-      const uint32_t va = tbase + v_off;
+      const uint32_t va = tbase + v_lo, vh = tbase + v_hi;
       constexpr int NSTEP = 2 * MBW, NGRP = NSTEP / 4;
       short4v lo[2][4], hi[2][4];
       static_for<4>([&](auto j) {
         constexpr int st = decltype(j)::value;
         constexpr int off = (16 * (st & 1)) * AB_ROW_BYTES + 64 * (st >> 1);
         lo[0][st] = lds_read_tr16_b64<off>(va);
-        hi[0][st] = lds_read_tr16_b64<off + 8 * AB_ROW_BYTES>(va);
+        hi[0][st] = lds_read_tr16_b64<off>(vh);
       });
       static_for<NGRP>([&](auto grp) {
         constexpr int G = decltype(grp)::value;
@@ -268,7 +251,7 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
             constexpr int st = 4 * (G + 1) + decltype(j)::value;
             constexpr int off = (16 * (st & 1)) * AB_ROW_BYTES + 64 * (st >> 1);
             lo[nxt][decltype(j)::value] = lds_read_tr16_b64<off>(va);
-            hi[nxt][decltype(j)::value] = lds_read_tr16_b64<off + 8 * AB_ROW_BYTES>(va);
+            hi[nxt][decltype(j)::value] = lds_read_tr16_b64<off>(vh);
           });
           lgkm_wait<8>(lo[cur][0], lo[cur][1], lo[cur][2], lo[cur][3]);
           lgkm_wait<8>(hi[cur][0], hi[cur][1], hi[cur][2], hi[cur][3]);
