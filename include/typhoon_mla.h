@@ -220,6 +220,9 @@ int typhoon_mla_combine_lse(int32_t num_partials, int64_t rows, int32_t width,
  *   bit 11 (0x800): the absorb attention kernel for more than 32 query rows per request walks
  *     every chunk with moving exponent references (otherwise only chunks in which its first walk,
  *     with references fixed at the chunk's first tokens, overflowed).
+ *   bit 12 (0x1000): requests with a multiple of 128 query rows keep the absorb kernel that
+ *     gives a workgroup 64 rows; bit 13 (0x2000): they take the 128-row kernel even when its
+ *     grid does not cover the chip (by default it is chosen only when it does).
  * Returns the previous value.
  */
 int typhoon_mla_set_debug_flags(int flags);

@@ -304,6 +304,12 @@ int mfma_absorb_attention(const Plan& p, const DecodeArgs& d) {
   a.max_blocks = d.max_blocks; a.block_size = d.block_size;
   a.rows = p.rows;
   a.c = d.sm_scale * LOG2E;
+  // 128 rows per workgroup when the request has whole blocks of them and the grid still covers
+  // the chip (debug flags: bit 12 keeps the 64-row kernel, bit 13 takes the 128-row kernel
+  // whatever the grid size)
+  if (a.R % 128 == 0 && !(debug_flags() & 0x1000) &&
+      ((debug_flags() & 0x2000) || (long long)p.n_lat * p.B * (a.R / 128) >= NUM_CU))
+    return mfma_absorb128_attention(p, d, a);
   if (a.R > 32) return mfma_absorb64_attention(p, d, a);
   static bool attr_set = false;
   if (!attr_set) {

@@ -121,5 +121,6 @@ __device__ __attribute__((always_inline)) inline void issue_all(const RowSrc& s,
 }
 
 int mfma_absorb64_attention(const Plan& p, const DecodeArgs& d, const AbsorbArgs& a);
+int mfma_absorb128_attention(const Plan& p, const DecodeArgs& d, const AbsorbArgs& a);
 
 }  // namespace tmla

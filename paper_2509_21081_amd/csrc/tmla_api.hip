@@ -36,7 +36,6 @@ static int check_dims(const tmla_dims* d) {
 
 static inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % a) != 0; }
 
-constexpr int NUM_CU = 256;  // MI355X compute units; work is cut to a small multiple of this
 
 // Token splits of a naive pass over Ls shared tokens for M queries per head.
 static void plan_prefix_splits(int H, int M, int Ls, int* p_chunk, int* np_split) {

@@ -9,6 +9,8 @@
 
 namespace tmla {
 
+constexpr int NUM_CU = 256;  // MI355X compute units; work is cut to a small multiple of this
+
 // DeepSeek-v3 / Kimi K2 MLA dimensions (paper Table 1).
 constexpr int D_L = 512;          // KV LoRA rank (latent width)
 constexpr int D_N = 128;          // noPE head dim

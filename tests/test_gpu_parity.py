@@ -163,6 +163,60 @@ def test_suffix_scores_far_from_the_first_step(gain, gpu_device, monkeypatch):
             assert np.array_equal(got, alone) and np.array_equal(got_lse, alone_lse)
 
 
+# requests with whole blocks of 128 query rows: (name, kwargs for small_spec)
+ROWS128_CASES = {
+    "h128": dict(batch=5, heads=128, q_len=1, prefix_len=300, suffix_min=40, suffix_max=330,
+                 seed=26),
+    # 256 rows = two workgroups per request; the causal edge runs through the rows
+    "h128_mtp": dict(batch=3, heads=128, q_len=2, prefix_len=70, suffix_min=1, suffix_max=200,
+                     seed=41),
+    # two query positions inside one workgroup's 128 rows, long enough for an odd number of steps
+    "h64_qlen2": dict(batch=4, heads=64, q_len=2, prefix_len=130, suffix_min=60, suffix_max=450,
+                      seed=42),
+    "h128_block128": dict(batch=2, heads=128, q_len=1, prefix_len=33, suffix_min=0,
+                          suffix_max=260, block_size=128, seed=43),
+}
+
+
+@pytest.mark.parametrize("chunk", [0, 64], ids=["auto_chunks", "chunk64"])
+@pytest.mark.parametrize("mode", ["mixed", "absorb_only"])
+@pytest.mark.parametrize("case", list(ROWS128_CASES))
+def test_absorb_kernel_with_128_rows_per_workgroup(case, mode, chunk, gpu_device, monkeypatch):
+    """The absorb kernel that gives a workgroup 128 query rows is chosen only for grids that cover
+    the chip; debug flag 0x2000 takes it at any size.  Parity with the oracle, and agreement with
+    the 64-row kernel (flag 0x1000) to the same tolerance."""
+    if chunk:
+        monkeypatch.setenv("TMLA_SUFFIX_CHUNK", str(chunk))
+        monkeypatch.setenv("TMLA_ABSORB_PREFIX_CHUNK", str(chunk))
+    wl = W.make_workload(W.small_spec(name=case, dtype="bf16", **ROWS128_CASES[case]))
+    ref, ref_lse = O.mla_decode_definition(**wl.as_float64())
+    print(f"128-row absorb kernel case={case} mode={mode} chunk={chunk}", flush=True)
+    got, got_lse = Hh.run_library(wl, mode, gpu_device, flags=0x2000)
+    Hh.assert_parity(got, got_lse, ref, ref_lse, "bf16", f"{case}/rows128/{mode}")
+    other, other_lse = Hh.run_library(wl, mode, gpu_device, flags=0x1000)
+    Hh.assert_parity(other, other_lse, ref, ref_lse, "bf16", f"{case}/rows64/{mode}")
+
+
+@pytest.mark.parametrize("gain", [256.0, 16.0, 1.0 / 64.0])
+def test_suffix_scores_far_from_the_first_step_128_rows(gain, gpu_device, monkeypatch):
+    """test_suffix_scores_far_from_the_first_step for the 128-row absorb kernel, whose second
+    walk takes exact maxima from a scores-only pass."""
+    monkeypatch.setenv("TMLA_SUFFIX_CHUNK", "4096")
+    spec = W.small_spec(name="suffix_growth_128", dtype="bf16", batch=4, heads=128, q_len=2,
+                        prefix_len=40, suffix_min=200, suffix_max=700, seed=92)
+    wl = W.make_workload(spec)
+    wl.pool[:, :, 512:] *= gain
+    for b in range(spec.batch):
+        wl.pool[int(wl.block_table[b, 0]), :, 512:] /= gain     # the first 64 tokens stay
+    ref, ref_lse = O.mla_decode_definition(**wl.as_float64())
+    print(f"suffix score growth, 128-row kernel, gain={gain}", flush=True)
+    lg = max(1.0, gain / 4.0)
+    for mode in ["mixed", "absorb_only"]:
+        got, got_lse = Hh.run_library(wl, mode, gpu_device, flags=0x2000)
+        Hh.assert_parity(got, got_lse, ref, ref_lse, "bf16", f"suffix_growth_128_{gain}/{mode}",
+                         logit_gain=lg)
+
+
 @pytest.mark.parametrize("flags", [0, 1], ids=["mfma", "scalar"])
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 @pytest.mark.parametrize("ntok", [1, 31, 64, 100, 300])

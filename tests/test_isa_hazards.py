@@ -1,8 +1,10 @@
-"""The software-pipelined prefix kernel writes its MFMAs in assembly, so nothing inserts the wait
-states the hardware needs between a vector-ALU write of a register and a matrix-core read of it.
-The kernel is arranged so that no such pair is ever adjacent; this test compiles it to assembly
-and checks that: no MFMA of that kernel reads a register that one of the few instructions in front
-of it wrote with the vector ALU (copies the register allocator may have placed there included)."""
+"""Two kernels (the software-pipelined prefix kernel and the 128-row absorb kernel) write their
+MFMAs in assembly, so nothing inserts the wait states the hardware needs between a vector-ALU
+write of a register and a matrix-core read of it.  The kernels are arranged so that no such pair
+is ever adjacent; this test compiles them to assembly and checks that: no MFMA of those kernels
+reads a register that one of the few instructions in front of it wrote with the vector ALU
+(copies the register allocator may have placed there included), and no vector-ALU instruction
+reads an MFMA's result right behind it."""
 import os
 import re
 import subprocess
@@ -12,7 +14,8 @@ import pytest
 
 from paper_2509_21081_amd import build as B
 
-KERNEL = "prefix_attn_pipelined_kernel"
+KERNELS = [("tmla_prefix_mfma.hip", "prefix_attn_pipelined_kernel"),
+           ("tmla_absorb128_mfma.hip", "absorb128_kernel")]
 LOOKBACK = 3      # instructions in front of an MFMA that must not write its operands
 
 
@@ -35,15 +38,15 @@ def _operands(line):
 _cache = {}
 
 
-def _kernel_instructions():
-    if "instrs" not in _cache:
-        src = os.path.join(B.CSRC, "tmla_prefix_mfma.hip")
+def _kernel_instructions(source, kernel):
+    if (source, kernel) not in _cache:
+        src = os.path.join(B.CSRC, source)
         with tempfile.TemporaryDirectory() as tmp:
             out = os.path.join(tmp, "k.s")
             subprocess.run([B.HIPCC, *B.FLAGS, "-S", "--cuda-device-only", "-o", out, src],
                            check=True, capture_output=True)
             text = open(out).read()
-        start = text.index("\n_ZN4tmla" + str(len(KERNEL)) + KERNEL)
+        start = text.index("\n_ZN4tmla" + str(len(kernel)) + kernel)
         end = text.index("s_endpgm", start)
         instrs = []
         for raw in text[start:end].split("\n"):
@@ -51,13 +54,14 @@ def _kernel_instructions():
             if not t or t.startswith(";") or t.startswith(".") or t.endswith(":"):
                 continue
             instrs.append(t.split(";")[0].strip())
-        _cache["instrs"] = instrs
-    return _cache["instrs"]
+        _cache[(source, kernel)] = instrs
+    return _cache[(source, kernel)]
 
 
+@pytest.mark.parametrize("source,kernel", KERNELS)
 @pytest.mark.skipif(not os.path.exists(B.HIPCC), reason="hipcc not available")
-def test_no_vector_write_right_in_front_of_an_assembly_mfma():
-    instrs = _kernel_instructions()
+def test_no_vector_write_right_in_front_of_an_assembly_mfma(source, kernel):
+    instrs = _kernel_instructions(source, kernel)
     n_mfma = 0
     for i, ins in enumerate(instrs):
         if not ins.startswith("v_mfma"):
@@ -78,12 +82,13 @@ def test_no_vector_write_right_in_front_of_an_assembly_mfma():
     assert n_mfma > 100     # the loop bodies were found
 
 
+@pytest.mark.parametrize("source,kernel", KERNELS)
 @pytest.mark.skipif(not os.path.exists(B.HIPCC), reason="hipcc not available")
-def test_no_vector_read_right_behind_an_assembly_mfma():
+def test_no_vector_read_right_behind_an_assembly_mfma(source, kernel):
     """The other direction: a vector-ALU instruction (a register copy, say) that reads what an
     MFMA a few instructions in front of it writes would see the old contents.  The kernel's own
     reads come a whole period later or behind a long run of idle slots."""
-    instrs = _kernel_instructions()
+    instrs = _kernel_instructions(source, kernel)
     behind = 8
     for i, ins in enumerate(instrs):
         op = ins.split()[0]
