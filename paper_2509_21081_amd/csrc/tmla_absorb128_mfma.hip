@@ -342,6 +342,9 @@ __global__ void __launch_bounds__(256, 1) absorb128_kernel(Absorb128Args args) {
           }
         }
         l += sum;
+        // (pinned: otherwise the additions sink behind the output product, with all 32
+        // probabilities kept in registers until then)
+        asm volatile("" : "+v"(l));
       }
       // Transposed cache fragments: one group per latent block mb (4 k-steps, lo and hi half
       // each), double buffered.  The first group does not depend on the probabilities and is
@@ -391,10 +394,12 @@ __global__ void __launch_bounds__(256, 1) absorb128_kernel(Absorb128Args args) {
           });
         });
       }
+      // (behind the loop the register allocator may store accumulators to scratch right away;
+      // the last MFMAs must have written them by then)
+      if (step + 1 == nstep) a128_drain();
     }
 
     // ---- denominators: the score owners publish theirs, everybody reads all four blocks
-    a128_drain();
     raw_barrier();   // everyone is past its last read of the probabilities
     {
       const float lt = sum_halves(l);
