@@ -115,6 +115,70 @@ struct FinalizeArgs {
   int64_t rows;
 };
 
+// The naive partials of a row for this lane (value columns 32 wave + 8 v4 + 4 g .. + 3), loaded
+// ahead of the projection so that the epilogue does not pay a memory round trip of its own.
+template <int NN>
+struct NaivePrefetch {
+  float lse[NN];
+  f32x4 o[NN][4];
+};
+template <int NN>
+__device__ inline void prefetch_naive(const FinalizeArgs& a, size_t row, int wave, int g,
+                                      NaivePrefetch<NN>& pre) {
+#pragma unroll
+  for (int i = 0; i < NN; i++) {
+    pre.lse[i] = a.naive_lse[(size_t)i * a.rows + row];
+    const float* src = a.naive_o + ((size_t)i * a.rows + row) * D_V + 32 * wave + 4 * g;
+#pragma unroll
+    for (int v4 = 0; v4 < 4; v4++) pre.o[i][v4] = *(const f32x4*)(src + 8 * v4);
+  }
+}
+// merge O_A (LSE l_a) with NN prefetched naive partials, normalise, store
+template <int NN>
+__device__ inline void finalize_tail_prefetched(const FinalizeArgs& a, size_t row, int wave, int g,
+                                                float l_a, float (&oa)[16],
+                                                const NaivePrefetch<NN>& pre) {
+  float m2 = l_a;
+#pragma unroll
+  for (int i = 0; i < NN; i++) m2 = fmaxf(m2, pre.lse[i]);
+  __bf16* dst = a.out + row * D_V + 32 * wave + 4 * g;
+  if (m2 == -INFINITY) {
+#pragma unroll
+    for (int v4 = 0; v4 < 4; v4++) {
+      bf16x4 w = {0, 0, 0, 0};
+      *(bf16x4*)(dst + 8 * v4) = w;
+    }
+    if (a.lse_out && wave == 0 && g == 0) a.lse_out[row] = -INFINITY;
+    return;
+  }
+  const float w_a = (l_a > -INFINITY) ? __expf(l_a - m2) : 0.f;
+  float z2 = w_a;
+#pragma unroll
+  for (int v = 0; v < 16; v++) oa[v] *= w_a;
+#pragma unroll
+  for (int i = 0; i < NN; i++) {
+    // (a partial with LSE = -inf was never written: it is skipped, not multiplied by zero)
+    if (pre.lse[i] == -INFINITY) continue;
+    const float w = __expf(pre.lse[i] - m2);
+    z2 += w;
+#pragma unroll
+    for (int v4 = 0; v4 < 4; v4++) {
+      const f32x4 x = pre.o[i][v4];
+      oa[4 * v4] += w * x[0]; oa[4 * v4 + 1] += w * x[1];
+      oa[4 * v4 + 2] += w * x[2]; oa[4 * v4 + 3] += w * x[3];
+    }
+  }
+  const float inv2 = 1.f / z2;
+#pragma unroll
+  for (int v4 = 0; v4 < 4; v4++) {
+    bf16x4 w;
+#pragma unroll
+    for (int e = 0; e < 4; e++) w[e] = (__bf16)(oa[4 * v4 + e] * inv2);
+    *(bf16x4*)(dst + 8 * v4) = w;
+  }
+  if (a.lse_out && wave == 0 && g == 0) a.lse_out[row] = m2 + __logf(z2);
+}
+
 // Steps shared by both finalize kernels: merge O_A (LSE l_a, this wavefront's 32 value columns
 // in oa) with the naive partials, normalise, store.
 __device__ inline void finalize_tail(const FinalizeArgs& a, size_t row, int wave, int g, float l_a,
@@ -231,7 +295,9 @@ __global__ void __launch_bounds__(256) finalize_kernel(FinalizeArgs a) {
 // suffix is rarely split more).  Nothing depends on anything but the loads, so all of them --
 // partial LSEs, weight fragments, latent partials -- are issued back to back and the kernel pays
 // one memory round trip instead of one per k-step; the merge weights live in registers.
-template <int NL>
+// NN > 0: the number of naive partials is NN and they are loaded up front with everything else
+// (0: any number, loaded in the epilogue).
+template <int NL, int NN>
 __global__ void __launch_bounds__(256) finalize_few_kernel(FinalizeArgs a) {
   __shared__ float red[4][4][16][64];        // [wavefront][value block][acc register][lane]
   const int h = blockIdx.x, qb = blockIdx.y;
@@ -257,6 +323,14 @@ __global__ void __launch_bounds__(256) finalize_few_kernel(FinalizeArgs a) {
 #pragma unroll
     for (int ks = 0; ks < 8; ks++)
       x[i][ks] = *(const bf16x8*)(lp + (size_t)i * a.rows * D_L + 16 * ks);
+  NaivePrefetch<(NN > 0 ? NN : 1)> pre;
+  if constexpr (NN > 0) {
+    prefetch_naive(a, row, wave, g, pre);
+#pragma unroll
+    for (int i = 0; i < NN; i++)
+      asm volatile("" : "+v"(pre.lse[i]), "+v"(pre.o[i][0]), "+v"(pre.o[i][1]), "+v"(pre.o[i][2]),
+                        "+v"(pre.o[i][3]));
+  }
 
   // pin every load above this point: without it the scheduler sinks the loads next to their
   // uses to save registers, and each k-step waits for its own round trip
@@ -320,7 +394,17 @@ __global__ void __launch_bounds__(256) finalize_few_kernel(FinalizeArgs a) {
     oa[v] = red[0][wave][v][lane] + red[1][wave][v][lane] + red[2][wave][v][lane] +
             red[3][wave][v][lane];
   if (!valid) return;
-  finalize_tail(a, row, wave, g, l_a, oa);
+  if constexpr (NN > 0) finalize_tail_prefetched(a, row, wave, g, l_a, oa, pre);
+  else finalize_tail(a, row, wave, g, l_a, oa);
+}
+
+template <int NL>
+static void launch_finalize_few(const FinalizeArgs& a, dim3 grid, hipStream_t stream) {
+  switch (a.n_naive) {
+    case 1: hipLaunchKernelGGL((finalize_few_kernel<NL, 1>), grid, dim3(256), 0, stream, a); break;
+    case 2: hipLaunchKernelGGL((finalize_few_kernel<NL, 2>), grid, dim3(256), 0, stream, a); break;
+    default: hipLaunchKernelGGL((finalize_few_kernel<NL, 0>), grid, dim3(256), 0, stream, a);
+  }
 }
 
 int mfma_finalize(const Plan& p, const DecodeArgs& d) {
@@ -337,10 +421,10 @@ int mfma_finalize(const Plan& p, const DecodeArgs& d) {
   a.M = p.B * p.Sq; a.H = p.H; a.n_naive = p.n_naive; a.n_lat = p.n_lat; a.rows = p.rows;
   dim3 grid(p.H, (a.M + 31) / 32);
   switch (p.n_lat) {
-    case 1: hipLaunchKernelGGL(finalize_few_kernel<1>, grid, dim3(256), 0, d.stream, a); break;
-    case 2: hipLaunchKernelGGL(finalize_few_kernel<2>, grid, dim3(256), 0, d.stream, a); break;
-    case 3: hipLaunchKernelGGL(finalize_few_kernel<3>, grid, dim3(256), 0, d.stream, a); break;
-    case 4: hipLaunchKernelGGL(finalize_few_kernel<4>, grid, dim3(256), 0, d.stream, a); break;
+    case 1: launch_finalize_few<1>(a, grid, d.stream); break;
+    case 2: launch_finalize_few<2>(a, grid, d.stream); break;
+    case 3: launch_finalize_few<3>(a, grid, d.stream); break;
+    case 4: launch_finalize_few<4>(a, grid, d.stream); break;
     default: hipLaunchKernelGGL(finalize_kernel, grid, dim3(256), 0, d.stream, a);
   }
   return TMLA_OK;
