@@ -19,12 +19,12 @@ typedef __attribute__((address_space(3))) short4v* lds_short4_ptr;
 // grid (H, 4 latent quarters, ceil(M/128)); 4 wavefronts x 32 queries.  W_UK[h] is [128, 512]
 // with the contraction index (noPE dim) as the row, i.e. k-major: a [128 x 128] slice is staged
 // in LDS and read through the transposing LDS load to form the A operand (rows = latent columns).
-constexpr int QA_ROW_BYTES = 288;  // 256 + 32: 4 consecutive rows land on distinct banks
+constexpr int QA_ROW_BYTES = 320;  // 256 + 64: 16 banks on per row, so the 4 rows x 64 B of a transposing read (32 lanes) cover the 64 banks once
 
 __global__ void __launch_bounds__(256) qabs_kernel(const __bf16* __restrict__ q,
                                                    const __bf16* __restrict__ w_uk,
                                                    __bf16* __restrict__ qabs, int M, int H) {
-  __shared__ __attribute__((aligned(16))) char wt[128 * QA_ROW_BYTES];
+  __shared__ __attribute__((aligned(16))) char wt[128 * QA_ROW_BYTES];   // 40 KiB; reused for the stores
   const int h = blockIdx.x, lq = blockIdx.y, qsb = blockIdx.z;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, g = lane >> 5;
   // stage W_UK[h][0:128][lq*128 : lq*128+128]: 128 rows x 16 chunks of 16 B
@@ -67,8 +67,13 @@ __global__ void __launch_bounds__(256) qabs_kernel(const __bf16* __restrict__ q,
       acc[mb] = mfma32(__builtin_bit_cast(bf16x8, both), qf[ks], acc[mb]);
     }
   }
-  if (valid) {
-    __bf16* dst = qabs + row * D_ROW + lq * 128;
+  // Store through LDS: a lane holds 8-byte pieces of its query's row, 16 bytes apart from its
+  // neighbour's; turned around in LDS (the staging buffer is free once everybody has its
+  // fragments), sixteen lanes write one query's 256 bytes of this latent quarter in one piece.
+  __syncthreads();
+  {
+    constexpr int ST_ROW = 272;   // 256 + 16: rows stay 16-byte aligned
+    char* mine = wt + wave * (32 * ST_ROW);
 #pragma unroll
     for (int mb = 0; mb < 4; mb++)
 #pragma unroll
@@ -76,8 +81,17 @@ __global__ void __launch_bounds__(256) qabs_kernel(const __bf16* __restrict__ q,
         bf16x4 w;
 #pragma unroll
         for (int e = 0; e < 4; e++) w[e] = (__bf16)acc[mb][4 * v4 + e];
-        *(bf16x4*)(dst + 32 * mb + 8 * v4 + 4 * g) = w;
+        *(bf16x4*)(mine + n * ST_ROW + (32 * mb + 8 * v4 + 4 * g) * 2) = w;
       }
+    // (each wavefront reads back only what it wrote itself: no barrier)
+    const int rr = lane >> 4, ch = lane & 15;
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+      const int r = 4 * i + rr;
+      const bf16x8 w = *(const bf16x8*)(mine + r * ST_ROW + ch * 16);
+      const int qq = (qsb * 4 + wave) * 32 + r;
+      if (qq < M) *(bf16x8*)(qabs + ((size_t)qq * H + h) * D_ROW + lq * 128 + ch * 8) = w;
+    }
   }
   if (lq == 0) {  // RoPE part: verbatim copy, 128 queries x 8 chunks
 #pragma unroll
