@@ -414,7 +414,10 @@ __global__ void __launch_bounds__(256) finalize_few_kernel(FinalizeArgs a) {
 
 template <int NL>
 static void launch_finalize_few(const FinalizeArgs& a, dim3 grid, hipStream_t stream) {
-  switch (a.n_naive) {
+  // The prefetch costs 34 registers, which halves the wavefronts per SIMD: it pays only where a
+  // compute unit gets so few workgroups that latency, not occupancy, sets the time.
+  const bool few_wgs = (long long)grid.x * grid.y <= 2 * NUM_CU;
+  switch (few_wgs ? a.n_naive : 0) {
     case 1: hipLaunchKernelGGL((finalize_few_kernel<NL, 1>), grid, dim3(256), 0, stream, a); break;
     case 2: hipLaunchKernelGGL((finalize_few_kernel<NL, 2>), grid, dim3(256), 0, stream, a); break;
     default: hipLaunchKernelGGL((finalize_few_kernel<NL, 0>), grid, dim3(256), 0, stream, a);
