@@ -57,6 +57,23 @@ __device__ inline void a128_mfma_s(f32x16& d, const bf16x8& a, const bf16x8& b) 
 __device__ inline void a128_mfma_o(f32x16& d, const bf16x8& a, const bf16x8& b) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b));
 }
+// The same behind a wait for LDS reads (at most N still in flight): one statement, so that
+// nothing is put between the wait and the MFMA.
+template <int N>
+__device__ inline void a128_mfma_s_first_w(f32x16& d, const bf16x8& a, const bf16x8& b) {
+  asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0"
+               : "=&v"(d) : "v"(a), "v"(b), "n"(N));
+}
+template <int N>
+__device__ inline void a128_mfma_s_w(f32x16& d, const bf16x8& a, const bf16x8& b) {
+  asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
+               : "+v"(d) : "v"(a), "v"(b), "n"(N));
+}
+template <int N>
+__device__ inline void a128_mfma_o_w(f32x16& d, const bf16x8& a, const bf16x8& b) {
+  asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
+               : "+a"(d) : "v"(a), "v"(b), "n"(N));
+}
 // enough idle issue slots for the last MFMA (16 passes) to have written its result
 __device__ inline void a128_drain() {
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");
@@ -243,9 +260,9 @@ __global__ void __launch_bounds__(256, 1) absorb128_kernel(Absorb128Args args) {
       constexpr int P = i >> 1;
       constexpr int KS = P < 32 ? 8 * (P & 3) + (P >> 2) : P;   // the k-step of this pair
       if constexpr (i + AHEAD < NF) rd(std::integral_constant<int, i + AHEAD>{});
-      lgkm_wait<(NF - 1 - i < AHEAD ? NF - 1 - i : AHEAD)>(fr[i % 8]);
-      if constexpr (i < 2) a128_mfma_s_first(sacc[i & 1], fr[i % 8], qf[KS]);
-      else a128_mfma_s(sacc[i & 1], fr[i % 8], qf[KS]);
+      constexpr int later = NF - 1 - i < AHEAD ? NF - 1 - i : AHEAD;   // younger requests
+      if constexpr (i < 2) a128_mfma_s_first_w<later>(sacc[i & 1], fr[i % 8], qf[KS]);
+      else a128_mfma_s_w<later>(sacc[i & 1], fr[i % 8], qf[KS]);
       if constexpr (i % 4 == 3) between(std::integral_constant<int, i / 4>{});
     });
     a128_drain();
@@ -384,12 +401,12 @@ __global__ void __launch_bounds__(256, 1) absorb128_kernel(Absorb128Args args) {
           static_for<8>([&](auto i_) {
             constexpr int i = decltype(i_)::value;   // MFMA i: k-step i / 2, query block i % 2
             constexpr int ks = i >> 1, q = i & 1;
-            if constexpr (q == 0) {
-              // requests behind those of fragment ks: 6 - 2 ks of this group, i of the next
-              constexpr int later = mb + 1 < 8 ? 6 : 6 - 2 * ks;
-              lgkm_wait<later>(trf[cur][2 * ks], trf[cur][2 * ks + 1]);
-            }
-            a128_mfma_o(o[mb][q], join_tr(trf[cur][2 * ks], trf[cur][2 * ks + 1]), pf[ks][q]);
+            // requests behind those of fragment ks: 6 - 2 ks of this group, i of the next
+            constexpr int later = mb + 1 < 8 ? 6 : 6 - 2 * ks;
+            if constexpr (q == 0)
+              a128_mfma_o_w<later>(o[mb][q], join_tr(trf[cur][2 * ks], trf[cur][2 * ks + 1]), pf[ks][q]);
+            else
+              a128_mfma_o(o[mb][q], join_tr(trf[cur][2 * ks], trf[cur][2 * ks + 1]), pf[ks][q]);
             if constexpr (mb + 1 < 8) rdv(std::integral_constant<int, mb + 1>{}, i_);
           });
         });
