@@ -193,6 +193,18 @@ __device__ inline void finalize_tail_prefetched(const FinalizeArgs& a, size_t ro
   if (a.lse_out && wave == 0 && g == 0) a.lse_out[row] = m2 + __logf(z2);
 }
 
+// Workgroup id -> (head, block of 32 queries).  The query blocks of a head read the same W_UV[h]:
+// they get ids 8 apart and consecutive in that stride, so they run at the same time on one XCD
+// (hardware deals consecutive ids round-robin over the 8 XCDs) and the weights come from HBM
+// once.
+__device__ inline bool finalize_item(const FinalizeArgs& a, int& h, int& qb) {
+  const int nqb = (a.M + 31) / 32;
+  const int id = blockIdx.x, x = id & 7, sl = id >> 3;
+  qb = sl % nqb;
+  h = (sl / nqb) * 8 + x;
+  return h < a.H;
+}
+
 // Steps shared by both finalize kernels: merge O_A (LSE l_a, this wavefront's 32 value columns
 // in oa) with the naive partials, normalise, store.
 __device__ inline void finalize_tail(const FinalizeArgs& a, size_t row, int wave, int g, float l_a,
@@ -241,7 +253,8 @@ __device__ inline void finalize_tail(const FinalizeArgs& a, size_t row, int wave
 __global__ void __launch_bounds__(256) finalize_kernel(FinalizeArgs a) {
   __shared__ float wtab[FIN_MAX_LAT][32];    // normalised merge weight of each latent partial
   __shared__ float red[4][4][16][64];        // [wavefront][value block][acc register][lane]
-  const int h = blockIdx.x, qb = blockIdx.y;
+  int h, qb;
+  if (!finalize_item(a, h, qb)) return;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, g = lane >> 5;
   const int qi = qb * 32 + n;
   const bool valid = qi < a.M;
@@ -314,7 +327,8 @@ __global__ void __launch_bounds__(256) finalize_kernel(FinalizeArgs a) {
 template <int NL, int NN>
 __global__ void __launch_bounds__(256) finalize_few_kernel(FinalizeArgs a) {
   __shared__ float red[4][4][16][64];        // [wavefront][value block][acc register][lane]
-  const int h = blockIdx.x, qb = blockIdx.y;
+  int h, qb;
+  if (!finalize_item(a, h, qb)) return;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, g = lane >> 5;
   const int qi = qb * 32 + n;
   const bool valid = qi < a.M;
@@ -416,7 +430,7 @@ template <int NL>
 static void launch_finalize_few(const FinalizeArgs& a, dim3 grid, hipStream_t stream) {
   // The prefetch costs 34 registers, which halves the wavefronts per SIMD: it pays only where a
   // compute unit gets so few workgroups that latency, not occupancy, sets the time.
-  const bool few_wgs = (long long)grid.x * grid.y <= 2 * NUM_CU;
+  const bool few_wgs = grid.x <= 2 * NUM_CU;
   switch (few_wgs ? a.n_naive : 0) {
     case 1: hipLaunchKernelGGL((finalize_few_kernel<NL, 1>), grid, dim3(256), 0, stream, a); break;
     case 2: hipLaunchKernelGGL((finalize_few_kernel<NL, 2>), grid, dim3(256), 0, stream, a); break;
@@ -436,7 +450,7 @@ int mfma_finalize(const Plan& p, const DecodeArgs& d) {
   a.out = (__bf16*)d.out;
   a.lse_out = d.lse_out;
   a.M = p.B * p.Sq; a.H = p.H; a.n_naive = p.n_naive; a.n_lat = p.n_lat; a.rows = p.rows;
-  dim3 grid(p.H, (a.M + 31) / 32);
+  dim3 grid(8 * ((a.M + 31) / 32) * ((p.H + 7) / 8));
   switch (p.n_lat) {
     case 1: launch_finalize_few<1>(a, grid, d.stream); break;
     case 2: launch_finalize_few<2>(a, grid, d.stream); break;
