@@ -382,9 +382,6 @@ __device__ inline void pl_mfma_o_w(f32x16& d, const bf16x8& a, const bf16x8& b) 
   asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
                : "+a"(d) : "v"(a), "v"(b), "n"(PL_D - 1));
 }
-__device__ inline void pl_mfma_l(f32x16& d, const bf16x8& a, const bf16x8& b) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "v"(b));
-}
 // enough idle issue slots for the last MFMA (16 passes) to have written its result
 __device__ inline void pl_mfma_drain() {
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");
@@ -478,14 +475,6 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
   };
 
   bf16x8 fr[8];          // fragment ring: fragment j of period t lives in fr[(4 (t & 1) + j) % 8]
-  // Denominators: every row of lacc[nb] holds, for this lane's query, the sum of the packed
-  // probabilities over all full blocks (a 32 x 16 matrix of ones times P^T); l[] only collects
-  // the partial last block.
-  f32x16 lacc[2];
-  bf16x8 ones8;
-#pragma unroll
-  for (int e = 0; e < 8; e++) ones8[e] = (__bf16)1.f;
-  asm volatile("" : "+v"(ones8));
   f32x16 sb[2][2];       // scores of blocks of even / odd index
   bf16x8 pb[2][2][2];    // probabilities of blocks of even / odd index
 
@@ -514,16 +503,18 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
     const int kg = t + PL_AHEAD;      // group issued in this period
 
     float xa = 0.f, xb = 0.f, ea = 0.f, eb = 0.f;
+    float sum[2] = {0.f, 0.f};   // denominators of block t, per column block
     // The softmax of block t, two scores (one packed pair of probabilities) per quantum, spread
     // so that no instruction waits for the one before it and no transcendental directly follows
     // an MFMA (either would cost idle issue slots):
     //   behind the first MFMA of quantum j : arguments of pair j
-    //   behind the second MFMA             : pack the pair of quantum j-1; e_a(j), e_b(j) = exp2
+    //   behind the second MFMA             : pack the pair of quantum j-1 and add it to the
+    //                                        denominator; e_a(j), e_b(j) = exp2
     // Pair k = elements 2 (k % 8), 2 (k % 8) + 1 of column block k / 8.  The empty statements pin
     // every piece where it is written (the results are only used much later, and would
-    // otherwise be moved down there).  The denominators are not summed here: the matrix core
-    // adds the packed probabilities up one period later (see pl_mfma_l below), which costs four
-    // MFMA issue slots per period instead of 32 additions.
+    // otherwise be moved down there).  (Summing the denominators on the matrix core instead -- a
+    // 32 x 16 matrix of ones times P^T, four more MFMAs per block for 32 additions less -- was 2 %
+    // slower: the kernel runs at the clock the power limit allows, and MFMAs are what draws it.)
     auto part1 = [&](auto j_tag) __attribute__((always_inline)) {
       constexpr int j = decltype(j_tag)::value;
       if constexpr (j < 16) {
@@ -541,6 +532,12 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
         p_out[nb][v0 / 8][v0 % 8] = pk[0];
         p_out[nb][v0 / 8][v0 % 8 + 1] = pk[1];
         asm volatile("" : "+v"(p_out[nb][v0 / 8]));
+        PL_SB();
+      }
+      if constexpr (j >= 1 && j <= 16) {
+        constexpr int nbp = (j - 1) / 8;
+        sum[nbp] += ea + eb;
+        asm volatile("" : "+v"(sum[nbp]));
         PL_SB();
       }
       if constexpr (j < 16) {
@@ -595,16 +592,14 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
         if constexpr (d >= 0 && d < 5) dma(std::integral_constant<int, (d >= 0 && d < 5) ? d : 0>{});
         PL_SB();
       });
-      if constexpr (j >= 16) {
-        // denominators of block t-1: ones (32 x 16) times P^T (16 tokens x 32 queries)
-        constexpr int nb = (j - 16) / 2, kk = (j - 16) % 2;
-        pl_mfma_l(lacc[nb], ones8, p_in[nb][kk]);
-        PL_SB();
-      }
     });
     // Control flow joins below and at the top of the next period, and register copies may be
     // placed there; the last MFMAs must have written their results before any such copy.
     pl_mfma_drain();
+    if (STEADY || t < nfull) {
+      l[0] += sum[0];
+      l[1] += sum[1];
+    }
   };
 
   // maximum of this lane's query over the first `limit` tokens of a block of scores, scaled
@@ -675,11 +670,6 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
       for (int e = 0; e < 8; e++) (&pb[0][0][0])[i][e] = (__bf16)0.f;
     asm volatile("" : "+v"(pb[0][0][0]), "+v"(pb[0][0][1]), "+v"(pb[0][1][0]), "+v"(pb[0][1][1]),
                       "+v"(pb[1][0][0]), "+v"(pb[1][0][1]), "+v"(pb[1][1][0]), "+v"(pb[1][1][1]));
-#pragma unroll
-    for (int nb = 0; nb < 2; nb++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) lacc[nb][v] = 0.f;
-    asm volatile("" : "+v"(lacc[0]), "+v"(lacc[1]));
     l[0] = l[1] = 0.f;
     for (int k = 0; k < PL_AHEAD - 1; k++) {
       dma_k(k, 0, GUARD{}); dma_k(k, 1, GUARD{}); dma_k(k, 2, GUARD{});
@@ -772,8 +762,8 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
     }
 
 
-    lt[0] = lacc[0][0] + sum_halves(l[0]);
-    lt[1] = lacc[1][0] + sum_halves(l[1]);
+    lt[0] = sum_halves(l[0]);
+    lt[1] = sum_halves(l[1]);
     if (attempt == 1) break;
     // a denominator that is not a moderate finite number: the references did not hold
     const bool bad_lane = !(lt[0] < 0x1p100f) || !(lt[1] < 0x1p100f);
