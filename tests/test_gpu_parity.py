@@ -310,8 +310,10 @@ def test_auto_mode_matches_oracle(case, gpu_device):
     Hh.assert_parity(got, got_lse, ref, ref_lse, "bf16", f"{case}/auto")
 
 
-@pytest.mark.parametrize("case", ["h128_many_tiles", "ragged_h16"])
-def test_decode_replays_from_a_hip_graph(case, gpu_device):
+@pytest.mark.parametrize("case,flags", [("h128_many_tiles", 0), ("ragged_h16", 0),
+                                        ("h128_many_tiles", 0x2000)],
+                         ids=["h128", "h16", "h128_rows128"])
+def test_decode_replays_from_a_hip_graph(case, flags, gpu_device):
     """The library only enqueues kernels on the caller's stream (no allocation, no host
     synchronisation, no memset nodes), so a decode step can be captured into a HIP graph.  Every
     replay, with eager work and synchronisations in between, must reproduce the eager result bit
@@ -334,27 +336,31 @@ def test_decode_replays_from_a_hip_graph(case, gpu_device):
                              suffix_lens=d.suffix_lens, max_suffix_len=wl.max_suffix_len,
                              w_uk=d.w_uk, w_uv=d.w_uv, out=out, lse_out=lse, workspace=ws)
 
-    print(f"graph capture case={case}", flush=True)
-    step()                                   # eager: also performs the one-time kernel set-up
-    torch.cuda.synchronize(gpu_device)
-    eager = (out.clone(), lse.clone())
-    Hh.assert_parity(out.double().cpu().numpy(), lse.double().cpu().numpy(), ref, ref_lse, "bf16",
-                     f"{case}/eager")
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
-        step()
-    for rep in range(3):
-        out.fill_(float("nan"))              # eager work between replays
-        lse.fill_(float("nan"))
+    print(f"graph capture case={case} flags={flags:#x}", flush=True)
+    old_flags = T.typhoon_mla_set_debug_flags(flags)   # 0x2000: the 128-row absorb kernel
+    try:
+        step()                                   # eager: also performs the one-time kernel set-up
         torch.cuda.synchronize(gpu_device)
+        eager = (out.clone(), lse.clone())
+        Hh.assert_parity(out.double().cpu().numpy(), lse.double().cpu().numpy(), ref, ref_lse, "bf16",
+                         f"{case}/eager")
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for rep in range(3):
+            out.fill_(float("nan"))              # eager work between replays
+            lse.fill_(float("nan"))
+            torch.cuda.synchronize(gpu_device)
+            graph.replay()
+            torch.cuda.synchronize(gpu_device)
+            assert torch.equal(out, eager[0]) and torch.equal(lse, eager[1]), f"replay {rep} differs"
+        # new queries written in place are picked up by the next replay
+        q.copy_(torch.flip(d.q, dims=[0]))
         graph.replay()
         torch.cuda.synchronize(gpu_device)
-        assert torch.equal(out, eager[0]) and torch.equal(lse, eager[1]), f"replay {rep} differs"
-    # new queries written in place are picked up by the next replay
-    q.copy_(torch.flip(d.q, dims=[0]))
-    graph.replay()
-    torch.cuda.synchronize(gpu_device)
-    flipped = (out.clone(), lse.clone())
-    step()
-    torch.cuda.synchronize(gpu_device)
-    assert torch.equal(out, flipped[0]) and torch.equal(lse, flipped[1])
+        flipped = (out.clone(), lse.clone())
+        step()
+        torch.cuda.synchronize(gpu_device)
+        assert torch.equal(out, flipped[0]) and torch.equal(lse, flipped[1])
+    finally:
+        T.typhoon_mla_set_debug_flags(old_flags)
