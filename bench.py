@@ -4,7 +4,9 @@
 A "step" is one pass of the whole hot path -- typhoon_mla_decode in mixed mode: naive prefix
 attention, query absorption, absorb suffix attention, up-projection and LSE combine -- over one
 batch of seeded synthetic input already resident in HBM.  The one-off prefix expansion is timed
-separately.  Prints ONE JSON line (see README for the fields).
+separately.  Prints ONE JSON line: metric, value (tokens/s over the whole batch), ms_per_step,
+config.workload, the per-kernel times, `roofline` for the dominant kernel and `cpu_baseline` (the
+fp64 oracle timed on the host).
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2_dsv3_b64]
                   [--modes mixed,absorb_only,naive_only] [--no-cpu-baseline] [--no-stages]
