@@ -290,11 +290,15 @@ __global__ void __launch_bounds__(256, 1) absorb128_kernel(Absorb128Args args) {
   float m = -INFINITY;   // exponent reference of this lane's query (log2 units)
   float ll[4];           // denominators of column n in the four query blocks
 
-  // One walk over the chunk with references fixed at its start: from step 0 (`exact` false; step
-  // 0 is already on its way) or given in m.  Returns false if a denominator left the float range.
-  auto walk = [&](bool exact) __attribute__((always_inline)) -> bool {
+  // A walk over the chunk with references fixed at its start: in the first attempt from step 0
+  // (already on its way), in the second (`exact`) the exact maxima.  One copy of the code for
+  // both, and the outputs leave in one place behind the loop: with two inlined walks the
+  // compiler merges their epilogues and hands 256 accumulation registers over through scratch
+  // memory (40 000 cycles per workgroup).
+  f32x16 o[8][2];   // [latent block of the own half][query block of the own pair]
+  for (int attempt = 0;; attempt++) {
+    const bool exact = attempt == 1;
     if (exact) issue_step(0);
-    f32x16 o[8][2];   // [latent block of the own half][query block of the own pair]
 #pragma unroll
     for (int mb = 0; mb < 8; mb++)
 #pragma unroll
@@ -426,13 +430,31 @@ __global__ void __launch_bounds__(256, 1) absorb128_kernel(Absorb128Args args) {
 #pragma unroll
     for (int q = 0; q < 4; q++) ll[q] = lbuf[q * 32 + n];
     __syncthreads();   // read before the next walk (or nothing) writes the region again
+    if (exact) break;
     // a denominator that is not a moderate finite number: the references did not hold.  Every
     // wavefront reads the same four vectors, so the verdict is the same in all of them.
-    if (!exact) {
+    {
       const bool bad = !(ll[0] < 0x1p100f) || !(ll[1] < 0x1p100f) || !(ll[2] < 0x1p100f) ||
                        !(ll[3] < 0x1p100f);
-      if (__builtin_amdgcn_ballot_w64(bad) != 0) return false;
+      if (__builtin_amdgcn_ballot_w64(bad) == 0) break;
     }
+    // exact maxima of every query over the chunk: scores-only pass, one step at a time
+    float mx = -INFINITY;
+    for (int step = 0; step < nstep; step++) {
+      raw_barrier();   // everyone is done with the tiles of the step before
+      issue_step(step);
+      vm_wait<0>();
+      raw_barrier();
+      f32x16 sacc[2];
+      scores(smem_base + ((step & 1) * 2) * A128_TILE_BYTES, sacc, [](auto) {});
+      mask(step, sacc);
+      mx = fmaxf(mx, row_max(sacc));
+    }
+    m = mx;
+    raw_barrier();
+  }
+
+  {
 #pragma unroll
     for (int q = 0; q < 2; q++) {
       const int r_local = (qg * 4 + 2 * qp + q) * 32 + n;
@@ -458,25 +480,6 @@ __global__ void __launch_bounds__(256, 1) absorb128_kernel(Absorb128Args args) {
       a.lat_lse[(size_t)item * a.rows + (int64_t)b * a.R + r_own] =
           lt > 0.f ? (m + fast_log2(lt)) * LN2 : -INFINITY;
     }
-    return true;
-  };
-
-  if (!walk(false)) {
-    // exact maxima of every query over the chunk: scores-only pass, one step at a time
-    float mx = -INFINITY;
-    for (int step = 0; step < nstep; step++) {
-      raw_barrier();   // everyone is done with the tiles of the step before
-      issue_step(step);
-      vm_wait<0>();
-      raw_barrier();
-      f32x16 sacc[2];
-      scores(smem_base + ((step & 1) * 2) * A128_TILE_BYTES, sacc, [](auto) {});
-      mask(step, sacc);
-      mx = fmaxf(mx, row_max(sacc));
-    }
-    m = mx;
-    raw_barrier();
-    walk(true);
   }
 }
 

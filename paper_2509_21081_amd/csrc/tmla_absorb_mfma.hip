@@ -304,15 +304,12 @@ int mfma_absorb_attention(const Plan& p, const DecodeArgs& d) {
   a.max_blocks = d.max_blocks; a.block_size = d.block_size;
   a.rows = p.rows;
   a.c = d.sm_scale * LOG2E;
-  // 128 rows per workgroup when the request has whole blocks of them, the grid still covers the
-  // chip and the chunks are long: the 128-row kernel takes a quarter less time per step and row
-  // but longer to start and finish, which pays from about a dozen 64-token steps per workgroup
-  // (measured: 16 steps -4 %, 8 steps +7 %, 64 and more -25 %).  Debug flags: bit 12 keeps the
-  // 64-row kernel, bit 13 takes the 128-row kernel whatever the grid and chunk size.
-  const int chunk = p.ap_chunks > 0 ? p.ap_chunk : p.as_chunk;
+  // 128 rows per workgroup when the request has whole blocks of them and the grid still covers
+  // the chip (measured against the 64-row kernel at L_n = 256 ... 4096: 4 to 25 % less time).
+  // Debug flags: bit 12 keeps the 64-row kernel, bit 13 takes the 128-row kernel whatever the
+  // grid size.
   if (a.R % 128 == 0 && !(debug_flags() & 0x1000) &&
-      ((debug_flags() & 0x2000) ||
-       ((long long)p.n_lat * p.B * (a.R / 128) >= NUM_CU && chunk >= 1024)))
+      ((debug_flags() & 0x2000) || (long long)p.n_lat * p.B * (a.R / 128) >= NUM_CU))
     return mfma_absorb128_attention(p, d, a);
   if (a.R > 32) return mfma_absorb64_attention(p, d, a);
   static bool attr_set = false;

@@ -47,7 +47,7 @@ def _kernel_instructions(source, kernel):
                            check=True, capture_output=True)
             text = open(out).read()
         start = text.index("\n_ZN4tmla" + str(len(kernel)) + kernel)
-        end = text.index("s_endpgm", start)
+        end = text.index("\n.Lfunc_end", start)     # (early exits put s_endpgm in the middle)
         instrs = []
         for raw in text[start:end].split("\n"):
             t = raw.strip()
