@@ -455,24 +455,35 @@ __global__ void __launch_bounds__(256, 1) absorb128_kernel(Absorb128Args args) {
   }
 
   {
+    // Outputs, normalised, go out through LDS (the tiles are no longer needed): a lane holds
+    // 8-byte pieces of its query's row, 16 bytes apart from its neighbour's; turned around, 32
+    // lanes write the 512 bytes a row has in this wavefront's latent half in one piece.  Rows
+    // whose denominator is zero get zeros (their LSE says that nothing is there).
+    constexpr int ST_ROW = 528;   // 512 + 16: rows stay 16-byte aligned
+    char* mine = smem + wave * (32 * ST_ROW);
+    const int rr = lane >> 5, ch = lane & 31;
 #pragma unroll
     for (int q = 0; q < 2; q++) {
-      const int r_local = (qg * 4 + 2 * qp + q) * 32 + n;
-      if (r_local >= a.R) continue;
-      const int64_t row = (int64_t)b * a.R + r_local;
       const float lt = ll[2 * qp + q];
-      if (lt > 0.f) {
-        const float inv = 1.f / lt;
-        __bf16* o_dst = a.lat_o + ((size_t)item * a.rows + row) * D_L + 256 * lh + 4 * g;
+      const float inv = lt > 0.f ? 1.f / lt : 0.f;
 #pragma unroll
-        for (int mb = 0; mb < 8; mb++)
+      for (int mb = 0; mb < 8; mb++)
 #pragma unroll
-          for (int v4 = 0; v4 < 4; v4++) {
-            bf16x4 w;
+        for (int v4 = 0; v4 < 4; v4++) {
+          bf16x4 w;
 #pragma unroll
-            for (int e = 0; e < 4; e++) w[e] = (__bf16)(o[mb][q][4 * v4 + e] * inv);
-            *(bf16x4*)(o_dst + 32 * mb + 8 * v4) = w;
-          }
+          for (int e = 0; e < 4; e++) w[e] = (__bf16)(o[mb][q][4 * v4 + e] * inv);
+          *(bf16x4*)(mine + n * ST_ROW + (32 * mb + 8 * v4 + 4 * g) * 2) = w;
+        }
+      // (each wavefront reads back only what it wrote itself: no barrier)
+      const int row0 = (qg * 4 + 2 * qp + q) * 32;
+#pragma unroll
+      for (int i = 0; i < 16; i++) {
+        const int r = 2 * i + rr;
+        const bf16x8 w = *(const bf16x8*)(mine + r * ST_ROW + ch * 16);
+        if (row0 + r < a.R)
+          *(bf16x8*)(a.lat_o + ((size_t)item * a.rows + (int64_t)b * a.R + row0 + r) * D_L +
+                     256 * lh + ch * 8) = w;
       }
     }
     if (g == 0 && r_own < a.R) {
