@@ -188,24 +188,30 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
   }
   // (barrier A of step 0 also tells that every wavefront has its fragments: slots 2, 3 are free)
 
-  // One walk over the chunk; `first` = step 0 is already on its way (issued above with the
-  // query blocks).  Returns false if the walk used fixed references and they did not hold.
-  auto walk = [&](auto fixed_tag, bool first) __attribute__((always_inline)) -> bool {
-    constexpr bool FIXED = decltype(fixed_tag)::value;
-    if (!first) {
+  // A walk over the chunk: the first attempt with fixed references (unless the debug switch asks
+  // for moving ones), its step 0 already on its way (issued above with the query blocks); a
+  // second one with moving references if the fixed ones did not hold.  One copy of the code for
+  // both and one epilogue behind the loop (written as a lambda inlined once per variant, every
+  // trip around the step loop and the hand-over of the accumulators to the merged epilogues
+  // cost extra).
+  f32x16 o[4][2];   // [latent block of the own quarter][query block]
+  float m[2];       // exponent references of column n in either query block
+  f32x4 ll;         // denominators [query block + 2 * token half] of column n
+  for (int attempt = 0;; attempt++) {
+    const bool fixed = attempt == 0 && !args.moving_only;
+    if (attempt > 0) {
       RowSrc s0, s1;
       step_src(0, s0, s1);
       issue_all(s0, smem, dl);
       issue_all(s1, smem + AB_TILE_BYTES, dl);
     }
-    f32x16 o[4][2];   // [latent block of the own quarter][query block]
   #pragma unroll
     for (int mb = 0; mb < 4; mb++)
   #pragma unroll
       for (int q = 0; q < 2; q++)
   #pragma unroll
         for (int v = 0; v < 16; v++) o[mb][q][v] = 0.f;
-    float m[2] = {-INFINITY, -INFINITY};   // exponent references of column n in either query block
+    m[0] = m[1] = -INFINITY;
     float m_use[2] = {0.f, 0.f};           // the same, 0 where no token is visible
     float l = 0.f;                         // denominator part: own query block, own token half
 
@@ -285,7 +291,7 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
         for (int v = 0; v < 16; v++)
           if (acc_row(v, g) >= limit) sacc[v] = -INFINITY;
       }
-      if (!FIXED || step == 0) {
+      if (!fixed || step == 0) {
         {
           float mx = sacc[0];
 #pragma unroll
@@ -311,7 +317,7 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
           m[q] = m_new;
         }
         // (in step 0 every accumulator is still zero: nothing to rescale)
-        if (!FIXED && step > 0 && __builtin_amdgcn_ballot_w64(grow) != 0) {
+        if (!fixed && step > 0 && __builtin_amdgcn_ballot_w64(grow) != 0) {
           alpha[0] = fast_exp2(alpha[0]);
           alpha[1] = fast_exp2(alpha[1]);
           l *= alpha[qb];
@@ -414,14 +420,16 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
     }
     lgkm_wait<0>();
     raw_barrier();
-    f32x4 ll = lds_read_f32x4(mx_rd);
+    ll = lds_read_f32x4(mx_rd);
     lgkm_wait<0>(ll);
-    if (FIXED) {
-      // a denominator that is not a moderate finite number: the fixed references did not hold.
-      // Every wavefront reads the same four vectors, so the verdict is the same in all of them.
-      const bool bad = !(ll[0] + ll[2] < 0x1p100f) || !(ll[1] + ll[3] < 0x1p100f);
-      if (__builtin_amdgcn_ballot_w64(bad) != 0) return false;
-    }
+    if (!fixed) break;
+    // a denominator that is not a moderate finite number: the fixed references did not hold.
+    // Every wavefront reads the same four vectors, so the verdict is the same in all of them.
+    const bool bad = !(ll[0] + ll[2] < 0x1p100f) || !(ll[1] + ll[3] < 0x1p100f);
+    if (__builtin_amdgcn_ballot_w64(bad) == 0) break;
+    raw_barrier();   // everyone has read the denominators before the next walk's maxima land there
+  }
+  {
   #pragma unroll
     for (int q = 0; q < 2; q++) {
       const int r_local = (qg * 2 + q) * 32 + n;
@@ -446,12 +454,6 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
         *l_dst = -INFINITY;   // the causal mask hid every token of this chunk from this query
       }
     }
-    return true;
-  };
-  if (args.moving_only) {
-    walk(std::false_type{}, true);
-  } else if (!walk(std::true_type{}, true)) {
-    walk(std::false_type{}, false);
   }
 }
 
