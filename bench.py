@@ -70,6 +70,25 @@ def event_time(fn, steps, warmup, torch):
     return e0.elapsed_time(e1) / steps
 
 
+def cold_time(fn, iters, torch, dev):
+    """Average device time per call when every call starts with cold caches: a 512 MiB fill (twice
+    the 256 MB last-level cache) runs before each call, outside the event pair that times it."""
+    flush = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+    pairs = []
+    for i in range(iters):
+        flush.fill_(i & 0xFF)
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        fn()
+        e1.record(stream)
+        pairs.append((e0, e1))
+    torch.cuda.synchronize()
+    del flush
+    return sum(a.elapsed_time(b) for a, b in pairs) / iters
+
+
 def read_traffic(workload, kernel):
     """HBM bytes per launch measured with rocprofv3 --pmc (profiles/hbm_traffic.txt), or None."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
@@ -238,6 +257,11 @@ def main():
             k = max(3, args.steps // 5)
             ms[m] = time_steps(lambda: step(m), k, max(1, args.warmup // 5), torch)
 
+    # the same step with the caches flushed before every call (the timed region above runs the
+    # steps back to back, so whatever fits the last-level cache -- weights, queries, partials,
+    # a short prefix -- stays there between steps: `value` is a cache-warm number)
+    ms_cold = cold_time(lambda: step("mixed"), 10, torch, dev)
+
     # ---- per-kernel device time (mixed mode), for the roofline of the dominant kernel
     stage_ms = {}
     if not args.no_stages and spec.dtype == "bf16":
@@ -269,6 +293,7 @@ def main():
                    "block_size": spec.block_size, "seed": spec.seed},
         "tflops": flops_mixed / (ms["mixed"] * 1e-3) / 1e12,
         "ms_per_step_by_mode": ms,
+        "ms_per_step_cold_cache": ms_cold,
         "speedup_vs_absorb_only": (ms["absorb_only"] / ms["mixed"]) if "absorb_only" in ms else None,
         "speedup_vs_naive_only": (ms["naive_only"] / ms["mixed"]) if "naive_only" in ms else None,
         "prefix_expand_ms": expand_ms,
