@@ -37,9 +37,14 @@ struct Absorb16Args {
   float c;                   // sm_scale * log2(e)
 };
 
-// private tile layout (same as the shared-tile kernel): latent rows at r * 1056 with the
-// 16-byte chunk c in slot c ^ ((r >> 2) & 1), then 32 x 128 B of rope with chunk c of row r in
-// slot c ^ (r & 7)
+// private tile layout: latent rows at r * 1056 with the 16-byte chunk c in slot
+// c ^ ((r >> 3) & 1), then 32 x 128 B of rope with chunk c of row r in slot c ^ ((r >> 1) & 7).
+// The LDS has 64 four-byte banks; a 16-byte read is served 16 lanes at a time, an 8-byte
+// transposing read 32 lanes at a time.  The row stride is 8 banks mod 64: the transposing reads
+// of the output product (8 rows x 32 B per 32 lanes) cover the banks exactly, and the score
+// product's 16 rows x 16 B per 16 lanes do so because rows r and r + 8 sit in different halves
+// of a 32-byte pair.  Rope rows of equal parity share 32 banks; the swizzle separates the eight
+// of them that a 16-lane group reads.
 constexpr int A16_ROW_BYTES = 1056;
 constexpr int A16_MAIN_BYTES = 32 * A16_ROW_BYTES;
 constexpr int A16_TILE_BYTES = A16_MAIN_BYTES + 32 * 128;   // 37888
@@ -118,7 +123,7 @@ __global__ void __launch_bounds__(256, 1) absorb16_kernel(Absorb16Args a) {
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(bt_cache)::"memory");
   }
   const int lane_off0 = lane << 4, lane_off1 = (lane ^ 1) << 4;
-  const int rope_ch = ((lane & 7) ^ ((lane >> 3) & 7)) << 4;
+  const int rope_ch = ((lane & 7) ^ (lane >> 4)) << 4;   // rope group 0; odd groups: ^ 64
   auto issue_tile = [&](int tile, auto prefix_tag) __attribute__((always_inline)) {
     constexpr bool PREFIX = decltype(prefix_tag)::value;
     const int tok0 = t0 + tile * 32;
@@ -136,7 +141,7 @@ __global__ void __launch_bounds__(256, 1) absorb16_kernel(Absorb16Args a) {
 #pragma unroll
     for (int r = 0; r < 32; r++) {
       const int rr = min(r, last);
-      const int loff = ((r >> 2) & 1) ? lane_off1 : lane_off0;
+      const int loff = ((r >> 3) & 1) ? lane_off1 : lane_off0;
       dma16(base + (size_t)rr * row_bytes + loff, slot + r * A16_ROW_BYTES);
     }
 #pragma unroll
@@ -144,9 +149,9 @@ __global__ void __launch_bounds__(256, 1) absorb16_kernel(Absorb16Args a) {
       const int rr = min(8 * j + (lane >> 3), last);
       const char* src;
       if constexpr (PREFIX)
-        src = (const char*)a.pr + (size_t)(tok0 + rr) * (D_R * 2) + rope_ch;
+        src = (const char*)a.pr + (size_t)(tok0 + rr) * (D_R * 2) + (rope_ch ^ ((j & 1) << 6));
       else
-        src = base + (size_t)rr * row_bytes + D_L * 2 + rope_ch;
+        src = base + (size_t)rr * row_bytes + D_L * 2 + (rope_ch ^ ((j & 1) << 6));
       dma16(src, slot + A16_MAIN_BYTES + j * 1024);
     }
   };
@@ -172,18 +177,19 @@ __global__ void __launch_bounds__(256, 1) absorb16_kernel(Absorb16Args a) {
 
   // ---- per-lane LDS addresses
   //   scores, latent k-step ks < 16, token block mb: row 16*mb + n, chunk 4*ks + q4
-  //       -> (16*mb + n)*1056 + ((q4 ^ sw) * 16) + 64*ks,  sw = (n >> 2) & 1 (16*mb does not change it)
-  //   rope k-step k < 2: chunk c = 4*k + q4 in slot c ^ (row & 7), row & 7 = n & 7
+  //       -> (16*mb + n)*1056 + ((q4 ^ sw) * 16) + 64*ks,  sw = (n >> 3) & 1 (16*mb does not change it)
+  //   rope k-step k < 2: chunk c = 4*k + q4 in slot c ^ ((row >> 1) & 7), the same for row n
+  //       and row 16 + n
   const uint32_t tbase = lds_addr(slot);
-  const uint32_t s_addr = tbase + n * A16_ROW_BYTES + ((q4 ^ ((n >> 2) & 1)) << 4);
+  const uint32_t s_addr = tbase + n * A16_ROW_BYTES + ((q4 ^ ((n >> 3) & 1)) << 4);
   uint32_t r_addr[2];
 #pragma unroll
   for (int k = 0; k < 2; k++)
-    r_addr[k] = tbase + A16_MAIN_BYTES + n * 128 + (((4 * k + q4) ^ (n & 7)) << 4);
+    r_addr[k] = tbase + A16_MAIN_BYTES + n * 128 + (((4 * k + q4) ^ ((n >> 1) & 7)) << 4);
   //   P V (transposing read inside the 16-lane group q4, r = lane % 16):
-  //     token row 16*half + 4*q4 + r/4, latent 16*mb + 4*(r%4); row swizzle bit = q4 & 1
+  //     token row 16*half + 4*q4 + r/4, latent 16*mb + 4*(r%4); row swizzle bit = q4 >> 1
   const uint32_t v_addr = tbase + (4 * q4 + (n >> 2)) * A16_ROW_BYTES +
-                          ((((n & 3) >> 1) ^ (q4 & 1)) << 4) + 8 * (n & 1);
+                          ((((n & 3) >> 1) ^ (q4 >> 1)) << 4) + 8 * (n & 1);
 
   f32x4 o[32];
 #pragma unroll

@@ -3,7 +3,7 @@
 The kernels place every 16-byte chunk of a cache row in a swizzled slot (so that both of their
 read patterns spread over the LDS banks) and compute the per-lane addresses of the transfers and
 of the reads from separate formulas.  This test restates those formulas (from the comments of
-tmla_absorb_tile.hpp and tmla_absorb128_mfma.hip), fills a model tile the way the transfers do and
+tmla_absorb_tile.hpp, tmla_absorb128_mfma.hip and tmla_absorb16_mfma.hip), fills a model tile the way the transfers do and
 checks that
   * every read returns the chunk the matrix-core operand layout wants, and
   * under the bank rules measured on the hardware (64 four-byte banks; a 16-byte read is served
@@ -147,6 +147,53 @@ def test_tile_reads_return_the_intended_chunks_without_bank_conflicts(tile, nmb,
                         assert (kind, r) == ("lat", row), (sel, kk, half, mb, lane)
                         assert chunk * 8 + (a & 15) // 2 == col, (sel, kk, half, mb, lane)
                     assert _conflict_free(addrs, 8, 32), f"transposing read {sel} {kk} {half} {mb}"
+
+
+def test_private_tile_of_the_16_row_kernel():
+    """tmla_absorb16_mfma.hip: latent row r at r * 1056, chunk c in slot c ^ ((r >> 3) & 1); rope
+    rows of 128 B behind, chunk c of row r in slot c ^ ((r >> 1) & 7).  Lane = n + 16 q of a
+    16x16x32 matrix-core operand: row n, k = 8 q + e."""
+    ROW, MAIN = 1056, 32 * 1056
+    img = {}
+    for r in range(32):                                   # one transfer per latent row
+        for lane in range(64):
+            img[r * ROW + lane * 16] = ("lat", r, lane ^ ((r >> 3) & 1))
+    for j in range(4):                                    # rope parts of rows 8 j .. 8 j + 7
+        for lane in range(64):
+            row = 8 * j + (lane >> 3)
+            ch = (((lane & 7) ^ (lane >> 4)) << 4) ^ ((j & 1) << 6)
+            assert ch >> 4 == (lane & 7) ^ ((row >> 1) & 7)
+            img[MAIN + j * 1024 + lane * 16] = ("rope", row, ch >> 4)
+    assert len(img) == 32 * 64 + 32 * 8
+    # scores: token block mb, latent k-step ks: row 16 mb + n, chunk 4 ks + q
+    for mb in range(2):
+        for ks in range(16):
+            addrs = [(l & 15) * ROW + (((l >> 4) ^ (((l & 15) >> 3) & 1)) << 4) + 64 * ks
+                     + 16 * ROW * mb for l in range(64)]
+            for l, a in enumerate(addrs):
+                assert img[a] == ("lat", 16 * mb + (l & 15), 4 * ks + (l >> 4))
+            assert _conflict_free(addrs, 16, 16), f"score read {mb} {ks}"
+        for k in range(2):
+            addrs = [MAIN + (l & 15) * 128 + (((4 * k + (l >> 4)) ^ (((l & 15) >> 1) & 7)) << 4)
+                     + 16 * 128 * mb for l in range(64)]
+            for l, a in enumerate(addrs):
+                assert img[a] == ("rope", 16 * mb + (l & 15), 4 * k + (l >> 4))
+            assert _conflict_free(addrs, 16, 16), f"rope read {mb} {k}"
+    # outputs: 16-lane group q, r = lane % 16 wants token row 16 half + 4 q + r / 4 and latent
+    # columns 16 mb + 4 (r % 4) .. + 3
+    for half in range(2):
+        for mb in range(32):
+            addrs = []
+            for l in range(64):
+                n, q = l & 15, l >> 4
+                addrs.append((4 * q + (n >> 2)) * ROW + ((((n & 3) >> 1) ^ (q >> 1)) << 4)
+                             + 8 * (n & 1) + 32 * mb + 16 * ROW * half)
+            for l, a in enumerate(addrs):
+                n, q = l & 15, l >> 4
+                kind, r, chunk = img[a & ~15]
+                assert (kind, r) == ("lat", 16 * half + 4 * q + (n >> 2))
+                assert chunk * 8 + (a & 15) // 2 == 16 * mb + 4 * (n & 3)
+            assert _conflict_free(addrs, 8, 32), f"transposing read {half} {mb}"
 
 
 def test_the_former_layout_had_two_way_conflicts():
