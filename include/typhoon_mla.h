@@ -223,6 +223,9 @@ int typhoon_mla_combine_lse(int32_t num_partials, int64_t rows, int32_t width,
  *   bit 12 (0x1000): requests with a multiple of 128 query rows keep the absorb kernel that
  *     gives a workgroup 64 rows; bit 13 (0x2000): they take the 128-row kernel even when its
  *     grid does not cover the chip (by default it is chosen only when it does).
+ *   bit 14 (0x4000): the absorb attention kernels start the requests with the longest suffix
+ *     first whatever the grid size (by default only when a pass has more workgroups than the
+ *     chip has compute units, and the batch has at most 4096 requests); bit 15 (0x8000): never.
  * Returns the previous value.
  */
 int typhoon_mla_set_debug_flags(int flags);

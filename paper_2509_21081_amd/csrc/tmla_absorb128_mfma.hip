@@ -98,6 +98,7 @@ __global__ void __launch_bounds__(256, 1) absorb128_kernel(Absorb128Args args) {
     if (j >= args.n_lat * args.B) return;
     item = j % args.n_lat;
     b = j / args.n_lat;
+    if (args.a.order) b = args.a.order[b];
   }
   const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -510,6 +511,7 @@ int mfma_absorb128_attention(const Plan& p, const DecodeArgs& d, const AbsorbArg
   const long long units = (long long)p.n_lat * p.B;
   const long long wgs = 8LL * args.nqg * ((units + 7) / 8);
   if (wgs > 0x7fffffffLL) return TMLA_ERR_UNSUPPORTED;
+  args.a.order = suffix_request_order(p, d, wgs);
   hipLaunchKernelGGL(absorb128_kernel, dim3((unsigned)wgs), dim3(256), A128_LDS_BYTES, d.stream, args);
   return TMLA_OK;
 }

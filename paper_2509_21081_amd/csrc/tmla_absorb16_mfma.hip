@@ -30,6 +30,7 @@ struct Absorb16Args {
   const __bf16* pool;        // [num_blocks, block_size, 576]
   const int32_t* block_table;
   const int32_t* lens;
+  const int32_t* order;      // blockIdx.y -> request, or nullptr (identity)
   __bf16* lat_o;             // [n_lat, rows, 512]
   float* lat_lse;            // [n_lat, rows]
   int Sq, H, R, Ls, ap_chunks, ap_chunk, as_chunks, as_chunk, ap_groups, max_blocks, block_size;
@@ -69,7 +70,7 @@ __device__ inline float sum_quads(float x) {
 
 __global__ void __launch_bounds__(256, 1) absorb16_kernel(Absorb16Args a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int grp = blockIdx.x, b = blockIdx.y;
+  const int grp = blockIdx.x, b = a.order ? a.order[blockIdx.y] : blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, n = lane & 15, q4 = lane >> 4;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const bool q_valid = n < a.R;
@@ -359,6 +360,7 @@ int mfma_absorb16_attention(const Plan& p, const DecodeArgs& d) {
     attr_set = true;
   }
   dim3 grid(a.ap_groups + (p.as_chunks + 3) / 4, p.B);
+  a.order = suffix_request_order(p, d, (long long)grid.x * grid.y);
   hipLaunchKernelGGL(absorb16_kernel, grid, dim3(256), A16_LDS_BYTES, d.stream, a);
   return TMLA_OK;
 }

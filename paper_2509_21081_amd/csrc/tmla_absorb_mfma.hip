@@ -29,7 +29,8 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
   constexpr int NLP = 4 / NQB;
   constexpr int MBW = 16 / NLP;  // 32-latent blocks owned by a wavefront
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int item = blockIdx.x, qg = blockIdx.y, b = blockIdx.z;
+  const int item = blockIdx.x, qg = blockIdx.y;
+  const int b = a.order ? a.order[blockIdx.z] : blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, g = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: transfer bookkeeping is SALU
   const int qb = wave % NQB, lp = wave / NQB;
@@ -287,6 +288,43 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
   }
 }
 
+// rank of every request by (suffix length descending, index ascending); order[rank] = request.
+// One wavefront per request: its lanes compare 64 other requests at a time and count votes
+// (a thread per request walking all lengths one by one is bound by the latency of each read:
+// 25 us for 512 requests).
+__global__ void __launch_bounds__(256) suffix_order_kernel(const int32_t* lens, int B,
+                                                           int32_t* order) {
+  const int lane = threadIdx.x & 63;
+  const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (b >= B) return;   // wavefront-uniform
+  const int mine = lens[b];
+  int rank = 0;
+#pragma unroll 8
+  for (int t0 = 0; t0 < B; t0 += 64) {
+    const int i = t0 + lane;
+    const int other = i < B ? lens[i] : mine;
+    const bool ahead = i < B && (other > mine || (other == mine && i < b));
+    rank += __popcll(__builtin_amdgcn_ballot_w64(ahead));
+  }
+  if (lane == 0) order[rank] = b;
+}
+
+// Workgroups are handed to the compute units in index order, each unit taking the next one when
+// it is free.  When there are more workgroups than units and the suffix lengths differ, the
+// pass ends with a few units working on late long requests while the rest idle; starting the
+// longest requests first evens that out.  Debug flags:
+// bit 14 orders whatever the grid size, bit 15 never orders.
+constexpr int ORDER_MAX_BATCH = 4096;   // the ranking is quadratic in the batch size
+const int32_t* suffix_request_order(const Plan& p, const DecodeArgs& d, long long wgs) {
+  if (p.as_chunks <= 0 || !d.suffix_lens || p.B < 2 || p.B > ORDER_MAX_BATCH) return nullptr;
+  if (debug_flags() & 0x8000) return nullptr;
+  if (wgs <= NUM_CU && !(debug_flags() & 0x4000)) return nullptr;
+  int32_t* order = (int32_t*)(d.ws + p.off_order);
+  hipLaunchKernelGGL(suffix_order_kernel, dim3((p.B + 3) / 4), dim3(256), 0, d.stream,
+                     d.suffix_lens, p.B, order);
+  return order;
+}
+
 int mfma_absorb_attention(const Plan& p, const DecodeArgs& d) {
   if (p.n_lat <= 0 || p.rows == 0) return TMLA_OK;
   if (p.Sq * p.H <= 16) return mfma_absorb16_attention(p, d);
@@ -297,6 +335,7 @@ int mfma_absorb_attention(const Plan& p, const DecodeArgs& d) {
   a.pool = (const __bf16*)d.suffix_pool;
   a.block_table = d.block_table;
   a.lens = d.suffix_lens;
+  a.order = nullptr;
   a.lat_o = (__bf16*)(d.ws + p.off_lat_o);
   a.lat_lse = (float*)(d.ws + p.off_lat_lse);
   a.Sq = p.Sq; a.H = p.H; a.R = p.Sq * p.H; a.Ls = p.Ls;
@@ -320,6 +359,7 @@ int mfma_absorb_attention(const Plan& p, const DecodeArgs& d) {
     attr_set = true;
   }
   dim3 grid(p.n_lat, 1, p.B);
+  a.order = suffix_request_order(p, d, (long long)p.n_lat * p.B);
   hipLaunchKernelGGL(absorb_attn_kernel<1>, grid, dim3(256), AB_LDS_BYTES, d.stream, a);
   return TMLA_OK;
 }

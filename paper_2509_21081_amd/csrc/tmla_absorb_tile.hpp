@@ -18,6 +18,7 @@ struct AbsorbArgs {
   const __bf16* pool;        // [num_blocks, block_size, 576]
   const int32_t* block_table;
   const int32_t* lens;
+  const int32_t* order;      // workgroup's request slot -> request, or nullptr (identity)
   __bf16* lat_o;             // [n_lat, rows, 512]
   float* lat_lse;            // [n_lat, rows]
   int Sq, H, R, Ls, ap_chunks, ap_chunk, as_chunk, max_blocks, block_size;

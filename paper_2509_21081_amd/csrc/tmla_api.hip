@@ -113,6 +113,7 @@ void layout_workspace(Plan* p) {
   p->off_naive_lse = off; off = align_up(off + (size_t)p->n_naive * p->rows * 4, 256);
   p->off_lat_o = off;     off = align_up(off + (size_t)p->n_lat * p->rows * D_L * esz, 256);
   p->off_lat_lse = off;   off = align_up(off + (size_t)p->n_lat * p->rows * 4, 256);
+  p->off_order = off;     off = align_up(off + (p->n_lat ? (size_t)p->B * 4 : 0), 256);
   p->total = off + 256;
 }
 

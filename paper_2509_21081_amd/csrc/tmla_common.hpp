@@ -83,7 +83,7 @@ struct Plan {
   int as_chunk;        //   tokens per chunk (multiple of block_size)
   int n_naive;         // = np_split + ns_chunks   (128-wide partials per row)
   int n_lat;           // = ap_chunks + as_chunks  (512-wide latent partials per row)
-  size_t off_qabs, off_naive_o, off_naive_lse, off_lat_o, off_lat_lse, total;
+  size_t off_qabs, off_naive_o, off_naive_lse, off_lat_o, off_lat_lse, off_order, total;
 };
 
 int debug_flags();   // current typhoon_mla_set_debug_flags value
@@ -120,6 +120,10 @@ int mfma_prefix_attention(const Plan& p, const DecodeArgs& a);
 int mfma_naive_suffix_attention(const Plan& p, const DecodeArgs& a);
 int mfma_query_absorb(const Plan& p, const DecodeArgs& a);
 int mfma_absorb_attention(const Plan& p, const DecodeArgs& a);
+// Requests sorted by suffix length, longest first (written to the workspace by a small kernel
+// on the call's stream), for a pass that launches `wgs` workgroups; nullptr = keep the order
+// of the batch.
+const int32_t* suffix_request_order(const Plan& p, const DecodeArgs& a, long long wgs);
 int mfma_absorb16_attention(const Plan& p, const DecodeArgs& a);   // S_q * H <= 16
 int mfma_finalize(const Plan& p, const DecodeArgs& a);
 constexpr int MAX_CHUNKS = 32;  // per-request chunk bound for each of the latent prefix / suffix

@@ -197,6 +197,38 @@ def test_absorb_kernel_with_128_rows_per_workgroup(case, mode, chunk, gpu_device
     Hh.assert_parity(other, other_lse, ref, ref_lse, "bf16", f"{case}/rows64/{mode}")
 
 
+ORDER_CASES = {
+    # one per absorb kernel: <= 16, <= 32, 64 and 128 query rows per workgroup
+    "h16": (dict(batch=9, heads=16, q_len=1, prefix_len=70, suffix_min=0, suffix_max=300,
+                 seed=61), 0),
+    "h32": (dict(batch=7, heads=32, q_len=1, prefix_len=40, suffix_min=1, suffix_max=200,
+                 seed=62), 0),
+    "h64_sq2": (dict(batch=6, heads=64, q_len=2, prefix_len=33, suffix_min=2, suffix_max=260,
+                     seed=63), 0x1000),
+    "h128": (dict(batch=5, heads=128, q_len=1, prefix_len=64, suffix_min=0, suffix_max=200,
+                  seed=64), 0x2000),
+}
+
+
+@pytest.mark.parametrize("mode", ["mixed", "absorb_only"])
+@pytest.mark.parametrize("case", list(ORDER_CASES))
+def test_longest_suffix_first_order_changes_nothing(case, mode, gpu_device):
+    """Grids with more workgroups than compute units start the requests with the longest suffix
+    first (a small kernel ranks them); debug flag 0x4000 does so at any grid size, 0x8000 never.
+    A request's result does not depend on when its workgroups run: parity with the oracle, and
+    bit-identical to the run in batch order."""
+    kw, kernel_flag = ORDER_CASES[case]
+    wl = W.make_workload(W.small_spec(name="order_" + case, dtype="bf16", **kw))
+    assert len(set(int(x) for x in wl.suffix_lens)) > 2     # ragged, with ties possible
+    ref, ref_lse = O.mla_decode_definition(**wl.as_float64())
+    print(f"longest-first order case={case} mode={mode}", flush=True)
+    got, got_lse = Hh.run_library(wl, mode, gpu_device, flags=0x4000 | kernel_flag)
+    Hh.assert_parity(got, got_lse, ref, ref_lse, "bf16", f"{case}/ordered/{mode}")
+    plain, plain_lse = Hh.run_library(wl, mode, gpu_device, flags=0x8000 | kernel_flag)
+    assert np.array_equal(got, plain, equal_nan=True)
+    assert np.array_equal(got_lse, plain_lse, equal_nan=True)
+
+
 @pytest.mark.parametrize("gain", [256.0, 16.0, 1.0 / 64.0])
 def test_suffix_scores_far_from_the_first_step_128_rows(gain, gpu_device, monkeypatch):
     """test_suffix_scores_far_from_the_first_step for the 128-row absorb kernel, whose second
