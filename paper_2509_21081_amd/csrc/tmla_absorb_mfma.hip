@@ -289,7 +289,7 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
 }
 
 // rank of every request by (suffix length descending, index ascending); order[rank] = request.
-// One wavefront per request: its lanes compare 64 other requests at a time and count votes
+// One wavefront per request: its lanes compare 64 other requests at a time and count
 // (a thread per request walking all lengths one by one is bound by the latency of each read:
 // 25 us for 512 requests).
 __global__ void __launch_bounds__(256) suffix_order_kernel(const int32_t* lens, int B,
@@ -298,14 +298,15 @@ __global__ void __launch_bounds__(256) suffix_order_kernel(const int32_t* lens, 
   const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (b >= B) return;   // wavefront-uniform
   const int mine = lens[b];
+  // per-lane counts first (independent loads, several in flight), one reduction at the end
   int rank = 0;
 #pragma unroll 8
-  for (int t0 = 0; t0 < B; t0 += 64) {
-    const int i = t0 + lane;
-    const int other = i < B ? lens[i] : mine;
-    const bool ahead = i < B && (other > mine || (other == mine && i < b));
-    rank += __popcll(__builtin_amdgcn_ballot_w64(ahead));
+  for (int i = lane; i < B; i += 64) {
+    const int other = lens[i];
+    rank += (other > mine || (other == mine && i < b)) ? 1 : 0;
   }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) rank += __shfl_xor(rank, off);
   if (lane == 0) order[rank] = b;
 }
 
