@@ -10,16 +10,23 @@
  *
  * Conventions for every entry point
  *   - Every data pointer is CALLER-OWNED DEVICE MEMORY, 16-byte aligned, dense in the stated
- *     layout.  The library allocates nothing, keeps no state between calls, never synchronises
- *     the host and enqueues work only on `stream` (a hipStream_t passed as void*, NULL = the
- *     default stream).  Results are ready when the stream reaches the end of the enqueued work.
+ *     layout.  The library allocates nothing, never synchronises the host and enqueues work only
+ *     on `stream` (a hipStream_t passed as void*, NULL = the default stream).  Results are ready
+ *     when the stream reaches the end of the enqueued work.
+ *   - State: none between calls, with two documented exceptions, both process-wide and both
+ *     changed only through their own entry points -- typhoon_mla_set_debug_flags and
+ *     typhoon_mla_set_tuning (development switches; a production caller touches neither).  The
+ *     first launch of a kernel on a device also raises that kernel's dynamic-LDS limit, once per
+ *     device.  Entry points may be called from several host threads.
  *   - Return value: a tmla_status.  Arguments are validated on the host before anything is
- *     launched, so argument errors are reported without touching the GPU.
+ *     launched, so argument errors are reported without touching the GPU.  TMLA_ERR_HIP reports a
+ *     failure of the library's own launches only: a HIP error already pending in the calling
+ *     thread at entry is neither cleared nor reported.
  *   - Supported dimensions: kv_lora_rank 512, qk_nope_dim 128, qk_rope_dim 64, v_head_dim 128
  *     (DeepSeek-v3 / Kimi K2, Table 1), num_heads a multiple of 16, paged block_size 64 or 128.
  *   - dtype TMLA_BF16: bf16 storage, fp32 accumulation and softmax.  TMLA_FP32: fp32 throughout.
  *   - RoPE is applied by the caller: q[..., 128:192] and every cached rope part arrive rotated
- *     (Algorithm 1 lists the query as "after W_Qb projection and RoPE").
+ *     (the inputs of Algorithm 1 are the query after its up-projection and rotation).
  *
  * Expanded ("naive") cache layout -- what typhoon_mla_expand_* writes and decode reads.
  *   TMLA_FP32: K [H, L, 192], V [H, L, 128], row-major.
@@ -47,7 +54,7 @@ typedef enum {
   TMLA_ERR_INVALID_ARG = 1,        /* null / negative / misaligned / inconsistent argument   */
   TMLA_ERR_UNSUPPORTED = 2,        /* dimensions, head count, block size or dtype not built  */
   TMLA_ERR_WORKSPACE_TOO_SMALL = 3,
-  TMLA_ERR_HIP = 4                 /* a launch failed; hipGetLastError() has the reason      */
+  TMLA_ERR_HIP = 4                 /* one of the library's own launches failed                 */
 } tmla_status;
 
 typedef enum {
@@ -106,9 +113,9 @@ int typhoon_mla_expand_pool(const tmla_dims* dims, int32_t num_blocks, int32_t b
  * the throughput T of this library's absorb kernel over a shared prefix and the bandwidth M of its
  * naive prefix kernel as measured on MI355X at the small batches where the two meet (about
  * 100 TFLOP/s and 5 TB/s, giving 5.9 / q_len; the measured cross-over at prefix 4096 /
- * suffix 512 lies between batch 4 and 8).  The environment
- * variable TMLA_AUTO_BATCH_THRESHOLD overrides it.  TMLA_MODE_AUTO uses mixed when
- * batch >= this value.
+ * suffix 512 lies between batch 4 and 8).  The environment variable
+ * TMLA_AUTO_BATCH_THRESHOLD, read once per process, overrides it.  TMLA_MODE_AUTO uses mixed
+ * when batch >= this value.
  */
 double typhoon_mla_auto_batch_threshold(int32_t q_len);
 
@@ -206,7 +213,8 @@ int typhoon_mla_combine_lse(int32_t num_partials, int64_t rows, int32_t width,
                             void* out, int32_t out_dtype, float* lse_out, void* stream);
 
 /*
- * Debug / tuning switches (process-wide, not thread-safe; default 0).
+ * Debug switches (process-wide; default 0; the switch itself is atomic, but a call that runs
+ * while another thread changes it may see either value).
  *   bit 0: run the scalar reference kernels instead of the matrix-core kernels for bf16.
  *   bits 1..3: scalar kernel for one stage only -- 2 query absorption, 4 absorb attention,
  *     8 up-projection + combine (the other stages stay on the matrix cores).
@@ -229,6 +237,22 @@ int typhoon_mla_combine_lse(int32_t num_partials, int64_t rows, int32_t width,
  * Returns the previous value.
  */
 int typhoon_mla_set_debug_flags(int flags);
+
+/*
+ * Tuning overrides of the launch plan (process-wide; 0 = the library's own choice, the default).
+ * The initial value of each key is read once from the environment variable of the same name
+ * with the prefix TMLA_ (TMLA_PREFIX_SPLITS, ...), when the first call needs it.  The workspace
+ * size depends on them: set them before typhoon_mla_decode_workspace_bytes, not between it and
+ * the decode call.  Returns the previous value, or -1 for an unknown key or a negative value.
+ */
+typedef enum {
+  TMLA_TUNE_PREFIX_SPLITS = 0,        /* token splits of the naive prefix pass                   */
+  TMLA_TUNE_SUFFIX_CHUNK = 1,         /* tokens per chunk of the absorb pass over the suffix     */
+  TMLA_TUNE_ABSORB_PREFIX_CHUNK = 2,  /* tokens per chunk of the absorb pass over the prefix     */
+  TMLA_TUNE_NAIVE_SUFFIX_CHUNK = 3,   /* tokens per chunk of the naive pass over the suffix      */
+  TMLA_TUNE_COUNT = 4
+} tmla_tuning_key;
+int typhoon_mla_set_tuning(int key, int value);
 
 #ifdef __cplusplus
 }

@@ -25,8 +25,9 @@ EXPORTS = [
     "typhoon_mla_expand_prefix", "typhoon_mla_expand_pool", "typhoon_mla_decode_workspace_bytes",
     "typhoon_mla_decode", "typhoon_mla_combine_lse", "typhoon_mla_set_debug_flags",
     "typhoon_mla_auto_batch_threshold", "typhoon_mla_decode_tree_workspace_bytes",
-    "typhoon_mla_decode_tree",
+    "typhoon_mla_decode_tree", "typhoon_mla_set_tuning",
 ]
+TUNE_PREFIX_SPLITS, TUNE_SUFFIX_CHUNK, TUNE_ABSORB_PREFIX_CHUNK, TUNE_NAIVE_SUFFIX_CHUNK = range(4)
 
 
 class tmla_dims(Structure):
@@ -94,6 +95,8 @@ def lib():
              c_size_t, c_void_p])
         L.typhoon_mla_set_debug_flags.restype = c_int
         L.typhoon_mla_set_debug_flags.argtypes = [c_int]
+        L.typhoon_mla_set_tuning.restype = c_int
+        L.typhoon_mla_set_tuning.argtypes = [c_int, c_int]
         _lib = L
     return _lib
 
@@ -127,6 +130,13 @@ def typhoon_mla_status_string(status):
 
 def typhoon_mla_set_debug_flags(flags):
     return lib().typhoon_mla_set_debug_flags(int(flags))
+
+
+def typhoon_mla_set_tuning(key, value):
+    old = lib().typhoon_mla_set_tuning(int(key), int(value))
+    if old < 0:
+        raise ValueError("typhoon_mla_set_tuning: unknown key %r or negative value %r" % (key, value))
+    return old
 
 
 def typhoon_mla_auto_batch_threshold(q_len=1):

@@ -496,13 +496,8 @@ __global__ void __launch_bounds__(256, 1) absorb128_kernel(Absorb128Args args) {
 }
 
 int mfma_absorb128_attention(const Plan& p, const DecodeArgs& d, const AbsorbArgs& a) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)absorb128_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            A128_LDS_BYTES) != hipSuccess)
-      return TMLA_ERR_HIP;
-    attr_set = true;
-  }
+  static LdsOptIn lds;
+  if (lds.ensure((const void*)absorb128_kernel, A128_LDS_BYTES) != hipSuccess) return TMLA_ERR_HIP;
   Absorb128Args args;
   args.a = a;
   args.nqg = (a.R + 127) / 128;

@@ -352,13 +352,8 @@ int mfma_absorb16_attention(const Plan& p, const DecodeArgs& d) {
   a.max_blocks = d.max_blocks; a.block_size = d.block_size;
   a.rows = p.rows;
   a.c = d.sm_scale * LOG2E;
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)absorb16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            A16_LDS_BYTES) != hipSuccess)
-      return TMLA_ERR_HIP;
-    attr_set = true;
-  }
+  static LdsOptIn lds;
+  if (lds.ensure((const void*)absorb16_kernel, A16_LDS_BYTES) != hipSuccess) return TMLA_ERR_HIP;
   dim3 grid(a.ap_groups + (p.as_chunks + 3) / 4, p.B);
   a.order = suffix_request_order(p, d, (long long)grid.x * grid.y);
   hipLaunchKernelGGL(absorb16_kernel, grid, dim3(256), A16_LDS_BYTES, d.stream, a);

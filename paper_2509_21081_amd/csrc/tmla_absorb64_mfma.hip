@@ -459,13 +459,8 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
 }
 
 int mfma_absorb64_attention(const Plan& p, const DecodeArgs& d, const AbsorbArgs& a) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)absorb64_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            A64_LDS_BYTES) != hipSuccess)
-      return TMLA_ERR_HIP;
-    attr_set = true;
-  }
+  static LdsOptIn lds;
+  if (lds.ensure((const void*)absorb64_kernel, A64_LDS_BYTES) != hipSuccess) return TMLA_ERR_HIP;
   Absorb64Args args;
   args.a = a;
   args.nqg = (a.R + 63) / 64;

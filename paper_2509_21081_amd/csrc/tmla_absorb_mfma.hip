@@ -352,13 +352,8 @@ int mfma_absorb_attention(const Plan& p, const DecodeArgs& d) {
       ((debug_flags() & 0x2000) || (long long)p.n_lat * p.B * (a.R / 128) >= NUM_CU))
     return mfma_absorb128_attention(p, d, a);
   if (a.R > 32) return mfma_absorb64_attention(p, d, a);
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)absorb_attn_kernel<1>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, AB_LDS_BYTES) != hipSuccess)
-      return TMLA_ERR_HIP;
-    attr_set = true;
-  }
+  static LdsOptIn lds;
+  if (lds.ensure((const void*)absorb_attn_kernel<1>, AB_LDS_BYTES) != hipSuccess) return TMLA_ERR_HIP;
   dim3 grid(p.n_lat, 1, p.B);
   a.order = suffix_request_order(p, d, (long long)p.n_lat * p.B);
   hipLaunchKernelGGL(absorb_attn_kernel<1>, grid, dim3(256), AB_LDS_BYTES, d.stream, a);

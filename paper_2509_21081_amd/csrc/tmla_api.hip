@@ -1,6 +1,7 @@
 // C ABI of the TyphoonMLA decode library: host-side argument validation, launch planning /
 // workspace layout, and dispatch to the kernels.  No HIP call is made before validation passes.
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 #include <vector>
@@ -9,18 +10,37 @@
 
 namespace tmla {
 
-static int g_debug_flags = 0;
-int debug_flags() { return g_debug_flags; }
+// The only state the library keeps: debug flags and tuning overrides, both process-wide, both
+// set through their own entry points (see typhoon_mla.h).
+static std::atomic<int> g_debug_flags{0};
+int debug_flags() { return g_debug_flags.load(std::memory_order_relaxed); }
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 static inline int round_up(int a, int b) { return ceil_div(a, b) * b; }
 
-static int env_int(const char* name, int dflt) {
-  const char* s = getenv(name);
-  if (!s || !*s) return dflt;
-  return atoi(s);
+// Tuning overrides; 0 = the library's own choice.  The environment gives the initial values and
+// is read once, when the first call needs them.
+struct Tuning {
+  std::atomic<int> v[TMLA_TUNE_COUNT];
+  double auto_threshold;   // < 0: closed form
+  Tuning() {
+    static const char* const names[TMLA_TUNE_COUNT] = {
+        "TMLA_PREFIX_SPLITS", "TMLA_SUFFIX_CHUNK", "TMLA_ABSORB_PREFIX_CHUNK",
+        "TMLA_NAIVE_SUFFIX_CHUNK"};
+    for (int i = 0; i < TMLA_TUNE_COUNT; i++) {
+      const char* s = getenv(names[i]);
+      v[i].store((s && *s) ? atoi(s) : 0);
+    }
+    const char* e = getenv("TMLA_AUTO_BATCH_THRESHOLD");
+    auto_threshold = (e && *e) ? atof(e) : -1.0;
+  }
+};
+static Tuning& tuning() {
+  static Tuning t;
+  return t;
 }
+static int tune(int key) { return tuning().v[key].load(std::memory_order_relaxed); }
 
 static int check_dims(const tmla_dims* d) {
   if (!d) return TMLA_ERR_INVALID_ARG;
@@ -40,7 +60,7 @@ static inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % 
 // Token splits of a naive pass over Ls shared tokens for M queries per head.
 static void plan_prefix_splits(int H, int M, int Ls, int* p_chunk, int* np_split) {
   const int wgs = std::max(1, H * (M > 128 ? ceil_div(M, 256) : ceil_div(M, 64)));
-  int splits = env_int("TMLA_PREFIX_SPLITS", 0);
+  int splits = tune(TMLA_TUNE_PREFIX_SPLITS);
   if (splits <= 0) splits = std::max(1, NUM_CU / wgs);
   splits = std::max(1, std::min(splits, ceil_div(Ls, 128)));
   *p_chunk = round_up(ceil_div(Ls, splits), TOK_BLK);
@@ -69,7 +89,7 @@ int make_plan(const tmla_dims* dims, int mode, int B, int Sq, int Ls, int max_su
     plan_prefix_splits(H, M, Ls, &p->p_chunk, &p->np_split);
   }
   if (mode == TMLA_MODE_NAIVE_ONLY && max_suffix > 0) {
-    int chunk = env_int("TMLA_NAIVE_SUFFIX_CHUNK", 0);
+    int chunk = tune(TMLA_TUNE_NAIVE_SUFFIX_CHUNK);
     if (chunk <= 0) chunk = 1024;
     p->ns_chunk = round_up(std::min(chunk, round_up(max_suffix, block_size)), block_size);
     p->ns_chunks = ceil_div(max_suffix, p->ns_chunk);
@@ -84,14 +104,14 @@ int make_plan(const tmla_dims* dims, int mode, int B, int Sq, int Ls, int max_su
     const int wgs = std::max(1, B * ceil_div(R, 64));
     const int want = std::max(1, ceil_div(2 * NUM_CU, wgs)) * per_wg;   // chunks per request
     if (mode == TMLA_MODE_ABSORB_ONLY && Ls > 0) {
-      int chunk = env_int("TMLA_ABSORB_PREFIX_CHUNK", 0);
+      int chunk = tune(TMLA_TUNE_ABSORB_PREFIX_CHUNK);
       if (chunk <= 0) chunk = std::max(256, ceil_div(Ls, want));
       chunk = std::max(chunk, ceil_div(Ls, MAX_CHUNKS));
       p->ap_chunk = round_up(std::min(chunk, round_up(Ls, TOK_BLK)), TOK_BLK);
       p->ap_chunks = ceil_div(Ls, p->ap_chunk);
     }
     if (max_suffix > 0) {
-      int chunk = env_int("TMLA_SUFFIX_CHUNK", 0);
+      int chunk = tune(TMLA_TUNE_SUFFIX_CHUNK);
       if (chunk <= 0) chunk = std::max(256, ceil_div(max_suffix, want));
       chunk = std::max(chunk, ceil_div(max_suffix, MAX_CHUNKS));
       p->as_chunk = round_up(std::min(chunk, round_up(max_suffix, block_size)), block_size);
@@ -138,10 +158,11 @@ const char* typhoon_mla_status_string(int status) {
   }
 }
 
-int typhoon_mla_set_debug_flags(int flags) {
-  const int old = g_debug_flags;
-  g_debug_flags = flags;
-  return old;
+int typhoon_mla_set_debug_flags(int flags) { return g_debug_flags.exchange(flags); }
+
+int typhoon_mla_set_tuning(int key, int value) {
+  if (key < 0 || key >= TMLA_TUNE_COUNT || value < 0) return -1;
+  return tuning().v[key].exchange(value);
 }
 
 size_t typhoon_mla_expanded_k_bytes(const tmla_dims* dims, int64_t num_tokens) {
@@ -164,12 +185,12 @@ static int expand_common(const tmla_dims* dims, int64_t ntok, const void* c, int
       misaligned(k_out, 16) || misaligned(v_out, 16))
     return TMLA_ERR_INVALID_ARG;
   hipStream_t st = (hipStream_t)stream;
-  (void)hipGetLastError();
+  const LaunchCheck launches;
   if (dims->dtype == TMLA_FP32) {
     simple_expand<float>(dims->num_heads, ntok, (const float*)c, c_stride, (const float*)r,
                          r_stride, (const float*)w_uk, (const float*)w_uv, (float*)k_out,
                          (float*)v_out, st);
-  } else if (g_debug_flags & 1) {
+  } else if (debug_flags() & 1) {
     simple_expand<bf16_t>(dims->num_heads, ntok, (const bf16_t*)c, c_stride, (const bf16_t*)r,
                           r_stride, (const bf16_t*)w_uk, (const bf16_t*)w_uv, (bf16_t*)k_out,
                           (bf16_t*)v_out, st);
@@ -178,7 +199,7 @@ static int expand_common(const tmla_dims* dims, int64_t ntok, const void* c, int
                                v_out, st);
     if (rc != TMLA_OK) return rc;
   }
-  return hipGetLastError() == hipSuccess ? TMLA_OK : TMLA_ERR_HIP;
+  return launches.status();
 }
 
 int typhoon_mla_expand_prefix(const tmla_dims* dims, int32_t prefix_len, const void* prefix_ckv,
@@ -224,8 +245,7 @@ static int check_decode_sizes(const tmla_dims* dims, int mode, int batch, int q_
 static constexpr double AUTO_T_FLOPS = 100e12, AUTO_M_BYTES = 5e12;
 
 double typhoon_mla_auto_batch_threshold(int32_t q_len) {
-  const char* e = getenv("TMLA_AUTO_BATCH_THRESHOLD");
-  if (e && *e) return atof(e);
+  if (tuning().auto_threshold >= 0.0) return tuning().auto_threshold;
   if (q_len <= 0) q_len = 1;
   // Section 3.2: L_s H (D_qk+D_v) w / M = B S_q L_s H (2 D_l + D_r) 2 / T  with w = 2 bytes
   return (double)(D_QK + D_V) / (q_len * (2.0 * D_L + D_R)) * AUTO_T_FLOPS / AUTO_M_BYTES;
@@ -301,44 +321,44 @@ int typhoon_mla_decode(const tmla_dims* dims, int32_t mode, int32_t batch, int32
   a.num_blocks = num_blocks; a.block_size = block_size; a.max_blocks = max_blocks;
   a.sm_scale = dims->sm_scale; a.stream = (hipStream_t)stream;
 
-  (void)hipGetLastError();
+  const LaunchCheck launches;
   if (dims->dtype == TMLA_FP32) {
     simple_stage_naive<float>(p, a, 0, p.n_naive);
     simple_stage_qabs<float>(p, a);
     simple_stage_absorb<float>(p, a);
     simple_stage_finalize<float>(p, a);
-  } else if (g_debug_flags & 1) {
+  } else if (debug_flags() & 1) {
     simple_stage_naive<bf16_t>(p, a, 0, p.n_naive);
     simple_stage_qabs<bf16_t>(p, a);
     simple_stage_absorb<bf16_t>(p, a);
     simple_stage_finalize<bf16_t>(p, a);
   } else {
     // bits 4..8 of the debug flags restrict the call to single stages (for per-kernel timing)
-    const int only = g_debug_flags & 0x1f0;
+    const int only = debug_flags() & 0x1f0;
     if (!only || (only & 0x10)) {
       st = mfma_prefix_attention(p, a);
       if (st != TMLA_OK) return st;
     }
     if (!only || (only & 0x20)) {
       // (bit 9 of the debug flags keeps the scalar kernel for this stage)
-      if ((g_debug_flags & 0x200) || p.Sq > 64)
+      if ((debug_flags() & 0x200) || p.Sq > 64)
         simple_stage_naive<bf16_t>(p, a, p.np_split, p.ns_chunks);
       else if ((st = mfma_naive_suffix_attention(p, a)) != TMLA_OK) return st;
     }
     if (!only || (only & 0x40)) {
-      if (g_debug_flags & 2) simple_stage_qabs<bf16_t>(p, a);
+      if (debug_flags() & 2) simple_stage_qabs<bf16_t>(p, a);
       else if ((st = mfma_query_absorb(p, a)) != TMLA_OK) return st;
     }
     if (!only || (only & 0x80)) {
-      if (g_debug_flags & 4) simple_stage_absorb<bf16_t>(p, a);
+      if (debug_flags() & 4) simple_stage_absorb<bf16_t>(p, a);
       else if ((st = mfma_absorb_attention(p, a)) != TMLA_OK) return st;
     }
     if (!only || (only & 0x100)) {
-      if (g_debug_flags & 8) simple_stage_finalize<bf16_t>(p, a);
+      if (debug_flags() & 8) simple_stage_finalize<bf16_t>(p, a);
       else if ((st = mfma_finalize(p, a)) != TMLA_OK) return st;
     }
   }
-  return hipGetLastError() == hipSuccess ? TMLA_OK : TMLA_ERR_HIP;
+  return launches.status();
 }
 
 // ---- tree-shaped shared prefixes -----------------------------------------------------------
@@ -442,7 +462,7 @@ int typhoon_mla_decode_tree(const tmla_dims* dims, int32_t batch, int32_t q_len,
   const bool bf16 = dims->dtype == TMLA_BF16;
   const size_t esz = bf16 ? 2 : 4;
 
-  (void)hipGetLastError();
+  const LaunchCheck launches;
   // every level slot starts empty; a node's pass fills the rows of its own requests
   launch_fill_f32((float*)(a.ws + p.off_naive_lse), (int64_t)p.n_naive * p.rows, -INFINITY, a.stream);
   for (int i = 0; i < num_nodes; i++) {
@@ -457,7 +477,7 @@ int typhoon_mla_decode_tree(const tmla_dims* dims, int32_t batch, int32_t q_len,
     DecodeArgs an = a;
     an.q = (const char*)q + (size_t)row0 * D_QK * esz;
     an.prefix_k = nd.k; an.prefix_v = nd.v;
-    if (bf16 && !(g_debug_flags & 1)) {
+    if (bf16 && !(debug_flags() & 1)) {
       if ((st = mfma_prefix_attention(pn, an)) != TMLA_OK) return st;
     } else if (bf16) {
       simple_stage_naive<bf16_t>(pn, an, 0, pn.np_split, (int64_t)nd.batch_count * q_len * dims->num_heads);
@@ -469,7 +489,7 @@ int typhoon_mla_decode_tree(const tmla_dims* dims, int32_t batch, int32_t q_len,
     simple_stage_qabs<float>(p, a);
     simple_stage_absorb<float>(p, a);
     simple_stage_finalize<float>(p, a);
-  } else if (g_debug_flags & 1) {
+  } else if (debug_flags() & 1) {
     simple_stage_qabs<bf16_t>(p, a);
     simple_stage_absorb<bf16_t>(p, a);
     simple_stage_finalize<bf16_t>(p, a);
@@ -478,7 +498,7 @@ int typhoon_mla_decode_tree(const tmla_dims* dims, int32_t batch, int32_t q_len,
     if ((st = mfma_absorb_attention(p, a)) != TMLA_OK) return st;
     if ((st = mfma_finalize(p, a)) != TMLA_OK) return st;
   }
-  return hipGetLastError() == hipSuccess ? TMLA_OK : TMLA_ERR_HIP;
+  return launches.status();
 }
 
 int typhoon_mla_combine_lse(int32_t num_partials, int64_t rows, int32_t width,
@@ -492,10 +512,10 @@ int typhoon_mla_combine_lse(int32_t num_partials, int64_t rows, int32_t width,
   if (misaligned(partial_out, 16) || misaligned(out, 8) || misaligned(partial_lse, 4) ||
       misaligned(lse_out, 4))
     return TMLA_ERR_INVALID_ARG;
-  (void)hipGetLastError();
+  const LaunchCheck launches;
   launch_combine_lse(num_partials, rows, width, partial_out, partial_lse, out, out_dtype, lse_out,
                      (hipStream_t)stream);
-  return hipGetLastError() == hipSuccess ? TMLA_OK : TMLA_ERR_HIP;
+  return launches.status();
 }
 
 }  // extern "C"

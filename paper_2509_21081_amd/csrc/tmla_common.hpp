@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/typhoon_mla.h"
 
 namespace tmla {
@@ -87,6 +89,35 @@ struct Plan {
 };
 
 int debug_flags();   // current typhoon_mla_set_debug_flags value
+
+// A kernel's opt-in to more dynamic LDS than the default limit, made once per device.  The
+// attribute call is idempotent, so two host threads racing here only repeat it.
+struct LdsOptIn {
+  std::atomic<uint64_t> done{0};
+  hipError_t ensure(const void* fn, int bytes) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
+    const uint64_t bit = (dev >= 0 && dev < 64) ? 1ull << dev : 0;
+    if (bit && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && bit) done.fetch_or(bit, std::memory_order_release);
+    return e;
+  }
+};
+
+// Reports the errors of the launches made while it is alive and nothing else: an error that was
+// already pending in the calling thread when the library was entered is the caller's and stays
+// where it is (the library neither clears nor reports it).
+struct LaunchCheck {
+  hipError_t before;
+  LaunchCheck() : before(hipPeekAtLastError()) {}
+  int status() const {
+    const hipError_t after = hipPeekAtLastError();
+    if (after == hipSuccess || after == before) return TMLA_OK;
+    if (before == hipSuccess) (void)hipGetLastError();   // ours: consumed here
+    return TMLA_ERR_HIP;
+  }
+};
 
 int make_plan(const tmla_dims* dims, int mode, int batch, int q_len, int prefix_len,
               int max_suffix_len, int block_size, Plan* plan);

@@ -242,13 +242,8 @@ int mfma_expand(int H, int64_t ntok, const void* c, int64_t c_stride, const void
   a.ntok = ntok; a.ntb = (ntok + TOK_BLK - 1) / TOK_BLK; a.H = H;
   a.tiles = (ntok + EX_TOK - 1) / EX_TOK;
   if (a.tiles * H > 0x7fffffff) return TMLA_ERR_UNSUPPORTED;
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)expand_gemm_kernel,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, EX_LDS_BYTES) != hipSuccess)
-      return TMLA_ERR_HIP;
-    attr_set = true;
-  }
+  static LdsOptIn lds;
+  if (lds.ensure((const void*)expand_gemm_kernel, EX_LDS_BYTES) != hipSuccess) return TMLA_ERR_HIP;
   hipLaunchKernelGGL(expand_gemm_kernel, dim3((unsigned)(a.tiles * H)), dim3(256), EX_LDS_BYTES,
                      stream, a);
   return TMLA_OK;

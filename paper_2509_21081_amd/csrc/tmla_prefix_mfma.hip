@@ -7,13 +7,19 @@
 // Q^T fragments stay in registers, S^T = K Q^T gives every lane 16 scores of one query, the
 // probabilities become the B operand of O^T = V^T P^T without any cross-lane traffic.
 //
-// Two workgroup shapes (4 wavefronts each):
-//   * query-split : the wavefronts own 4 x 64 different queries and share each K/V block through
-//     LDS (register-staged double buffer).  Used when a head has more than 128 queries; this is
-//     the MFMA-bound regime (intensity = number of queries per fetched byte).
-//   * token-split : all wavefronts own the same <= 64 queries and stream disjoint token blocks
-//     straight from global memory into registers (no LDS, no barriers in the loop); their partial
-//     softmaxes are merged through LDS at the end.  Used for small batches, the HBM-bound regime.
+// Three workgroup shapes; every K/V block goes global -> LDS with global_load_lds transfers
+// (no staging registers):
+//   * pipelined   : four wavefronts own 4 x 64 different queries of a head and share each block
+//     through LDS rings (K and V separately, all 160 KiB); one hand-laid instruction stream per
+//     wavefront overlaps the scores of block t+1, the softmax of block t and P V of block t-1.
+//     Used when a head has more than 128 queries: the MFMA-bound regime (intensity = number of
+//     queries per fetched byte).
+//   * query-split : the same split of the queries over eight wavefronts (two per SIMD) with
+//     moving exponent references, scheduled by the compiler; kept as the debug alternative.
+//   * token-split : all four wavefronts own the same <= 64 queries and stream disjoint token
+//     blocks, each through a private two-slot LDS ring (no barriers in the loop); their partial
+//     softmaxes are merged through LDS at the end.  Used for small batches, the HBM-bound regime,
+//     and (PAGED) for the expanded paged suffix of naive_only mode.
 // Split-K over the prefix comes on top (grid.z); each workgroup writes a normalised partial
 // output and its natural-log LSE for the combine step.
 #include <type_traits>
@@ -1050,28 +1056,15 @@ int mfma_prefix_attention(const Plan& p, const DecodeArgs& d) {
   a.blocks_per_split = p.p_chunk / TOK_BLK;
   a.rows = p.rows;
   a.c = d.sm_scale * LOG2E;
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)prefix_attn_query_split_kernel<1>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, QS_LDS_BYTES) != hipSuccess ||
-        hipFuncSetAttribute((const void*)prefix_attn_token_split_kernel<false>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, TS_LDS_BYTES) != hipSuccess ||
-        hipFuncSetAttribute((const void*)prefix_attn_token_split_kernel<true>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, TS_LDS_BYTES) != hipSuccess)
-      return TMLA_ERR_HIP;
-    attr_set = true;
-  }
+  static LdsOptIn lds_pl, lds_qs, lds_ts;
   if (a.M > 128 && !(debug_flags() & 0x400)) {
-    static bool pl_attr = false;
-    if (!pl_attr) {
-      if (hipFuncSetAttribute((const void*)prefix_attn_pipelined_kernel,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, PL_LDS_BYTES) != hipSuccess)
-        return TMLA_ERR_HIP;
-      pl_attr = true;
-    }
+    if (lds_pl.ensure((const void*)prefix_attn_pipelined_kernel, PL_LDS_BYTES) != hipSuccess)
+      return TMLA_ERR_HIP;
     dim3 grid(p.H, (a.M + PL_QUERIES - 1) / PL_QUERIES, p.np_split);
     hipLaunchKernelGGL(prefix_attn_pipelined_kernel, grid, dim3(256), PL_LDS_BYTES, d.stream, a);
   } else if (a.M > 128) {
+    if (lds_qs.ensure((const void*)prefix_attn_query_split_kernel<1>, QS_LDS_BYTES) != hipSuccess)
+      return TMLA_ERR_HIP;
     dim3 grid(p.H, (a.M + QS_QUERIES - 1) / QS_QUERIES, p.np_split);
     // NB = 1 measured faster than NB = 2 on every configuration: vector-ALU and matrix-core
     // instructions of a SIMD issue serially, so hiding LDS and barrier latency with a second
@@ -1079,6 +1072,8 @@ int mfma_prefix_attention(const Plan& p, const DecodeArgs& d) {
     hipLaunchKernelGGL(prefix_attn_query_split_kernel<1>, grid, dim3(512), QS_LDS_BYTES, d.stream,
                        a);
   } else {
+    if (lds_ts.ensure((const void*)prefix_attn_token_split_kernel<false>, TS_LDS_BYTES) != hipSuccess)
+      return TMLA_ERR_HIP;
     dim3 grid(p.H, (a.M + 63) / 64, p.np_split);
     hipLaunchKernelGGL(prefix_attn_token_split_kernel<false>, grid, dim3(256), TS_LDS_BYTES, d.stream, a);
   }
@@ -1104,13 +1099,9 @@ int mfma_naive_suffix_attention(const Plan& p, const DecodeArgs& d) {
   a.block_table = d.block_table; a.lens = d.suffix_lens; a.max_blocks = d.max_blocks;
   a.page_shift = d.block_size == 64 ? 1 : 2;
   a.Sq = p.Sq; a.first_slot = p.np_split;
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)prefix_attn_token_split_kernel<true>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, TS_LDS_BYTES) != hipSuccess)
-      return TMLA_ERR_HIP;
-    attr_set = true;
-  }
+  static LdsOptIn lds;
+  if (lds.ensure((const void*)prefix_attn_token_split_kernel<true>, TS_LDS_BYTES) != hipSuccess)
+    return TMLA_ERR_HIP;
   dim3 grid(p.H, p.B, p.ns_chunks);
   hipLaunchKernelGGL(prefix_attn_token_split_kernel<true>, grid, dim3(256), TS_LDS_BYTES, d.stream, a);
   return TMLA_OK;

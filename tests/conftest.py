@@ -18,3 +18,16 @@ def gpu_device():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     return torch.device("cuda:0")
+
+
+@pytest.fixture
+def tune():
+    """tune(key, value): sets a launch-plan override of the library for the rest of the test."""
+    from paper_2509_21081_amd import binding as T
+    saved = []
+
+    def _set(key, value):
+        saved.append((key, T.typhoon_mla_set_tuning(key, value)))
+    yield _set
+    for key, old in reversed(saved):
+        T.typhoon_mla_set_tuning(key, old)

@@ -79,11 +79,11 @@ def test_small_cases(case, dtype, mode, flags, gpu_device):
 @pytest.mark.parametrize("mode", ["mixed", "absorb_only"])
 @pytest.mark.parametrize("case", ["h128_many_tiles", "mtp_h32", "h48_mtp_empty_block",
                                   "ragged_h16"])
-def test_forced_small_chunks(case, mode, gpu_device, monkeypatch):
+def test_forced_small_chunks(case, mode, gpu_device, tune):
     """Token chunks of one 64-token step (32 tokens for the <= 16-row kernel's wavefront shares):
     every chunk boundary, empty chunks of short requests and the merge of many latent partials."""
-    monkeypatch.setenv("TMLA_SUFFIX_CHUNK", "64")
-    monkeypatch.setenv("TMLA_ABSORB_PREFIX_CHUNK", "64")
+    tune(T.TUNE_SUFFIX_CHUNK, 64)
+    tune(T.TUNE_ABSORB_PREFIX_CHUNK, 64)
     wl, (ref, ref_lse) = _workload_and_ref(case, "bf16")
     print(f"forced chunks case={case} mode={mode}", flush=True)
     got, got_lse = Hh.run_library(wl, mode, gpu_device)
@@ -93,12 +93,12 @@ def test_forced_small_chunks(case, mode, gpu_device, monkeypatch):
 
 @pytest.mark.parametrize("flags", [0, 0x400], ids=["pipelined", "8-wave"])
 @pytest.mark.parametrize("prefix_len", [31, 32, 40, 288, 1024, 1100])
-def test_pipelined_prefix_kernel_long_runs(prefix_len, flags, gpu_device, monkeypatch):
+def test_pipelined_prefix_kernel_long_runs(prefix_len, flags, gpu_device, tune):
     """More than 128 queries per head select the software-pipelined prefix kernel; one split
     (forced) makes a single workgroup walk the whole prefix: a partial block only, one full
     block, full + partial, one block more than the transfer look-ahead, and long runs with and
     without a partial tail.  Also with the 8-wavefront kernel, its fallback, running alone."""
-    monkeypatch.setenv("TMLA_PREFIX_SPLITS", "1")
+    tune(T.TUNE_PREFIX_SPLITS, 1)
     spec = W.small_spec(name=f"pipe_{prefix_len}", dtype="bf16", batch=200, heads=16, q_len=1,
                         prefix_len=prefix_len, suffix_min=0, suffix_max=40, seed=41 + prefix_len)
     wl = W.make_workload(spec)
@@ -109,7 +109,7 @@ def test_pipelined_prefix_kernel_long_runs(prefix_len, flags, gpu_device, monkey
 
 
 @pytest.mark.parametrize("gain,first", [(256.0, 64), (256.0, 1000), (16.0, 64), (1.0 / 64.0, 64)])
-def test_prefix_scores_far_from_the_first_block(gain, first, gpu_device, monkeypatch):
+def test_prefix_scores_far_from_the_first_block(gain, first, gpu_device, tune):
     """The RoPE part of the keys from token `first` on is scaled by `gain` (a power of two, and
     that part of a key is stored as given, so the oracle sees exactly what the kernels see): the
     scores there lie far above (or below) those of the first block, whose maximum the pipelined
@@ -117,7 +117,7 @@ def test_prefix_scores_far_from_the_first_block(gain, first, gpu_device, monkeyp
     query: it must notice, form the exact maxima in a scores-only pass and walk the prefix
     again.  The 8-wavefront kernel (moving references; debug flag 0x400) is held against the
     oracle on the same inputs."""
-    monkeypatch.setenv("TMLA_PREFIX_SPLITS", "1")
+    tune(T.TUNE_PREFIX_SPLITS, 1)
     spec = W.small_spec(name="growth", dtype="bf16", batch=150, heads=16, q_len=1,
                         prefix_len=1100, suffix_min=0, suffix_max=30, seed=77)
     wl = W.make_workload(spec)
@@ -135,14 +135,14 @@ def test_prefix_scores_far_from_the_first_block(gain, first, gpu_device, monkeyp
 
 
 @pytest.mark.parametrize("gain", [256.0, 16.0, 1.0 / 64.0])
-def test_suffix_scores_far_from_the_first_step(gain, gpu_device, monkeypatch):
+def test_suffix_scores_far_from_the_first_step(gain, gpu_device, tune):
     """The same for the absorb pass over the suffix with more than 32 query rows per request: the
     64-row kernel first walks a chunk with exponent references fixed at its first 64 tokens and
     walks it again with moving references if its denominators overflowed.  The RoPE part of every
     cached suffix row behind the first block is scaled (stored as given, so exact for the
     oracle); one chunk per request (forced), so with gain 256 every workgroup overflows and the
     result is bit-identical to the walk with moving references alone (debug flag 0x800)."""
-    monkeypatch.setenv("TMLA_SUFFIX_CHUNK", "4096")
+    tune(T.TUNE_SUFFIX_CHUNK, 4096)
     spec = W.small_spec(name="suffix_growth", dtype="bf16", batch=6, heads=128, q_len=1,
                         prefix_len=40, suffix_min=200, suffix_max=700, seed=91)
     wl = W.make_workload(spec)
@@ -181,13 +181,13 @@ ROWS128_CASES = {
 @pytest.mark.parametrize("chunk", [0, 64], ids=["auto_chunks", "chunk64"])
 @pytest.mark.parametrize("mode", ["mixed", "absorb_only"])
 @pytest.mark.parametrize("case", list(ROWS128_CASES))
-def test_absorb_kernel_with_128_rows_per_workgroup(case, mode, chunk, gpu_device, monkeypatch):
+def test_absorb_kernel_with_128_rows_per_workgroup(case, mode, chunk, gpu_device, tune):
     """The absorb kernel that gives a workgroup 128 query rows is chosen only for grids that cover
     the chip; debug flag 0x2000 takes it at any size.  Parity with the oracle, and agreement with
     the 64-row kernel (flag 0x1000) to the same tolerance."""
     if chunk:
-        monkeypatch.setenv("TMLA_SUFFIX_CHUNK", str(chunk))
-        monkeypatch.setenv("TMLA_ABSORB_PREFIX_CHUNK", str(chunk))
+        tune(T.TUNE_SUFFIX_CHUNK, chunk)
+        tune(T.TUNE_ABSORB_PREFIX_CHUNK, chunk)
     wl = W.make_workload(W.small_spec(name=case, dtype="bf16", **ROWS128_CASES[case]))
     ref, ref_lse = O.mla_decode_definition(**wl.as_float64())
     print(f"128-row absorb kernel case={case} mode={mode} chunk={chunk}", flush=True)
@@ -230,10 +230,10 @@ def test_longest_suffix_first_order_changes_nothing(case, mode, gpu_device):
 
 
 @pytest.mark.parametrize("gain", [256.0, 16.0, 1.0 / 64.0])
-def test_suffix_scores_far_from_the_first_step_128_rows(gain, gpu_device, monkeypatch):
+def test_suffix_scores_far_from_the_first_step_128_rows(gain, gpu_device, tune):
     """test_suffix_scores_far_from_the_first_step for the 128-row absorb kernel, whose second
     walk takes exact maxima from a scores-only pass."""
-    monkeypatch.setenv("TMLA_SUFFIX_CHUNK", "4096")
+    tune(T.TUNE_SUFFIX_CHUNK, 4096)
     spec = W.small_spec(name="suffix_growth_128", dtype="bf16", batch=4, heads=128, q_len=2,
                         prefix_len=40, suffix_min=200, suffix_max=700, seed=92)
     wl = W.make_workload(spec)

@@ -124,6 +124,22 @@ def test_workspace_bytes_monotone_and_zero_on_error():
     assert big >= 64 * 128 * 576 * 2
 
 
+def test_tuning_overrides_change_the_plan_and_are_restored():
+    d = _dims(num_heads=128)
+    L = T.lib()
+    assert L.typhoon_mla_set_tuning(99, 1) == -1 and L.typhoon_mla_set_tuning(-1, 1) == -1
+    assert L.typhoon_mla_set_tuning(T.TUNE_SUFFIX_CHUNK, -5) == -1
+    base = T.typhoon_mla_decode_workspace_bytes(d, T.MODE_MIXED, 64, 1, 4096, 2048)
+    old = T.typhoon_mla_set_tuning(T.TUNE_SUFFIX_CHUNK, 64)
+    try:
+        # 32 chunks of 64 tokens per request instead of a few long ones: more latent partials
+        assert T.typhoon_mla_decode_workspace_bytes(d, T.MODE_MIXED, 64, 1, 4096, 2048) > base
+        assert T.typhoon_mla_set_tuning(T.TUNE_SUFFIX_CHUNK, old) == 64
+    finally:
+        T.typhoon_mla_set_tuning(T.TUNE_SUFFIX_CHUNK, old)
+    assert T.typhoon_mla_decode_workspace_bytes(d, T.MODE_MIXED, 64, 1, 4096, 2048) == base
+
+
 def test_combine_validation():
     L = T.lib()
     one = ctypes.c_void_p(4096)
