@@ -17,6 +17,11 @@ formulation (Section 2.1 "Absorb"; Algorithm 1 steps 5-7 applied to the whole ca
 pinned to the definition by the naive == absorb invariant in the CPU tests and is used where the
 definition is too expensive (its cost per token-head is 1088 MACs instead of 131072).
 
+`mla_decode_absorb_all_heads` is the same absorb formulation written the way Algorithm 1 prints
+it -- whole tensors, all heads of a request at once (steps 5, 6, 7 as three matrix products) --
+so that it is cheap enough to cover every output row of the full-size configurations.  It is
+pinned to the definition by the same invariant and by the scalar brute force.
+
 `combine_lse` is the LSE merge of Algorithm 1 step 8 written from its definition; it is used
 only to pin that "merge of split softmaxes == one softmax" and to check the GPU merge kernel.
 
@@ -150,6 +155,46 @@ def mla_decode_absorb_form(q, prefix_ckv, prefix_krope, pool, block_table, suffi
                 x = sm_scale * (c_all[:n_vis] @ q_a + r_all[:n_vis] @ q_rope)
                 o_lat, lse[b, s, h] = softmax_attend(x, c_all[:n_vis])
                 out[b, s, h] = w_uv[h] @ o_lat
+    return out, lse
+
+
+def mla_decode_absorb_all_heads(q, prefix_ckv, prefix_krope, pool, block_table, suffix_lens,
+                                w_uk, w_uv, sm_scale, requests=None):
+    """Absorb formulation in Algorithm 1's tensor form, one request at a time, all heads at once.
+
+    For request b and query position s, with C_N / C_R the visible latent and rope rows:
+      step 5   Q_A = Q_N W_KVb1              [H, 512]   (per head: q_nope W_UK[h])
+      step 6   P   = softmax(sm_scale (Q_A C_N^T + Q_R C_R^T))   [H, n_visible]
+               O_lat = P C_N                 [H, 512]
+      step 7   O   = O_lat W_KVb2^T          [H, 128]   (per head: W_UV[h] o_lat)
+    requests: optional iterable of b; other requests stay NaN.  Returns (O, LSE) like
+    `mla_decode_definition`.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    B, S_q, H, _ = q.shape
+    L_s = prefix_ckv.shape[0]
+    out = np.full((B, S_q, H, D_V), np.nan)
+    lse = np.full((B, S_q, H), np.nan)
+    for b in (range(B) if requests is None else requests):
+        len_b = int(suffix_lens[b])
+        rows = gather_suffix_rows(pool, block_table[b], len_b)
+        c_all = np.concatenate([prefix_ckv, rows[:, :D_LATENT]], axis=0)
+        r_all = np.concatenate([prefix_krope, rows[:, D_LATENT:]], axis=0)
+        for s in range(S_q):
+            n_vis = L_s + _visible_suffix(len_b, S_q, s)
+            if n_vis == 0:
+                out[b, s] = 0.0
+                lse[b, s] = -np.inf
+                continue
+            q_n, q_r = q[b, s, :, :D_NOPE], q[b, s, :, D_NOPE:]
+            q_a = np.einsum("hn,hnl->hl", q_n, w_uk)                       # step 5
+            x = sm_scale * (q_a @ c_all[:n_vis].T + q_r @ r_all[:n_vis].T)  # [H, n_vis]
+            m = np.max(x, axis=1)
+            e = np.exp(x - m[:, None])
+            z = np.sum(e, axis=1)
+            o_lat = (e / z[:, None]) @ c_all[:n_vis]                       # step 6
+            out[b, s] = np.einsum("hl,hvl->hv", o_lat, w_uv)               # step 7
+            lse[b, s] = m + np.log(z)
     return out, lse
 
 

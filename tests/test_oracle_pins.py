@@ -98,6 +98,49 @@ def test_I1_naive_equals_absorb(q_len, prefix_len):
     assert np.array_equal(np.isfinite(l_a), fin)
 
 
+@pytest.mark.parametrize("q_len,prefix_len", [(1, 37), (2, 20), (3, 0)])
+def test_I1_all_heads_absorb_form_equals_definition(q_len, prefix_len):
+    """The tensor-form absorb checker (all heads of a request at once) against the naive
+    definition, on the same ragged inputs as the per-row absorb form: empty suffixes, queries
+    that see nothing, poisoned storage behind every request's last token."""
+    wl = _wl(batch=3, heads=4, q_len=q_len, prefix_len=prefix_len, suffix_min=0, suffix_max=70,
+             block_size=16, seed=7 + q_len)
+    a = _args(wl)
+    o_n, l_n = O.mla_decode_definition(**a)
+    o_a, l_a = O.mla_decode_absorb_all_heads(**a)
+    np.testing.assert_allclose(o_a, o_n, rtol=1e-10, atol=1e-13)
+    fin = np.isfinite(l_n)
+    np.testing.assert_allclose(l_a[fin], l_n[fin], rtol=0, atol=1e-11)
+    assert np.array_equal(np.isneginf(l_a), np.isneginf(l_n)) and not np.isnan(o_a).any()
+    # a subset of requests leaves the others untouched
+    o_s, l_s = O.mla_decode_absorb_all_heads(**a, requests=[2])
+    np.testing.assert_array_equal(o_s[2], o_a[2])
+    assert np.isnan(o_s[:2]).all() and np.isnan(l_s[:2]).all()
+
+
+def test_I4_all_heads_absorb_form_against_brute_force():
+    wl = _wl(batch=2, heads=2, q_len=2, prefix_len=3, suffix_min=1, suffix_max=4, block_size=2,
+             seed=5)
+    a = _args(wl)
+    out, lse = O.mla_decode_absorb_all_heads(**a)
+    for b in range(2):
+        for s in range(2):
+            for h in range(2):
+                o_bf, l_bf = _brute_force(a, b, s, h)
+                np.testing.assert_allclose(out[b, s, h], o_bf, rtol=1e-10, atol=1e-13)
+                assert abs(lse[b, s, h] - l_bf) < 1e-11
+
+
+def test_I5_all_heads_absorb_form_causal_rows():
+    # S_q = 3, suffix lengths 5, 2, 0 and no prefix (see test_I5_causal_mask_and_empty_rows)
+    a = _tiny(0, [5, 2, 0], S_q=3, seed=8)
+    out, lse = O.mla_decode_absorb_all_heads(**a)
+    assert np.all(out[1, 0] == 0) and np.all(np.isneginf(lse[1, 0]))
+    row0 = a["pool"][a["block_table"][1, 0], 0]
+    np.testing.assert_allclose(out[1, 1, 0], a["w_uv"][0] @ row0[:512], rtol=1e-12)
+    assert np.all(out[2] == 0) and np.all(np.isneginf(lse[2])) and not np.any(np.isnan(out))
+
+
 # ---------------------------------------------------------------- I2: split + merge == full
 def _partial(a, b, s, h, idx_tokens):
     """softmax restricted to a subset of the visible tokens, via the oracle's own pieces."""
