@@ -54,7 +54,9 @@ typedef enum {
   TMLA_ERR_INVALID_ARG = 1,        /* null / negative / misaligned / inconsistent argument   */
   TMLA_ERR_UNSUPPORTED = 2,        /* dimensions, head count, block size or dtype not built  */
   TMLA_ERR_WORKSPACE_TOO_SMALL = 3,
-  TMLA_ERR_HIP = 4                 /* one of the library's own launches failed                 */
+  TMLA_ERR_HIP = 4,                /* one of the library's own launches failed                 */
+  TMLA_ERR_SCRATCH_LIMIT = 5       /* typhoon_mla_decode_static_scratch: the call needs more
+                                      than TMLA_STATIC_SCRATCH_BYTES of scratch memory       */
 } tmla_status;
 
 typedef enum {
@@ -155,6 +157,34 @@ int typhoon_mla_decode(const tmla_dims* dims, int32_t mode, int32_t batch, int32
                        const void* w_uk, const void* w_uv,
                        void* out, float* lse_out,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * typhoon_mla_decode for callers that cannot allocate device memory and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results and kernels as typhoon_mla_decode, without `workspace`: the
+ * intermediates (absorbed queries, split partials, the request order) live in a static device
+ * array of TMLA_STATIC_SCRATCH_BYTES inside the library, one per GPU the library runs on, held
+ * until the process ends.  The call allocates nothing and frees nothing.
+ *   - A problem whose typhoon_mla_decode_workspace_bytes exceeds TMLA_STATIC_SCRATCH_BYTES is
+ *     rejected with TMLA_ERR_SCRATCH_LIMIT before anything is launched (128 MiB covers batch 256
+ *     at 128 heads, batch 128 with q_len 2, and batch 512 at 16 heads with suffixes up to 4096).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two host threads) race on it; serialise them.  Nothing in it has to start at
+ *     zero -- every call writes what it reads -- so a call may follow any other.
+ *   - The first call on a device looks the array's address up; make that call outside graph
+ *     capture.
+ */
+#define TMLA_STATIC_SCRATCH_BYTES (128u << 20)
+int typhoon_mla_decode_static_scratch(const tmla_dims* dims, int32_t mode, int32_t batch,
+                                      int32_t q_len, const void* q, int32_t prefix_len,
+                                      const void* prefix_k, const void* prefix_v,
+                                      const void* prefix_ckv, const void* prefix_krope,
+                                      const void* suffix_pool, int32_t num_blocks,
+                                      int32_t block_size, const int32_t* block_table,
+                                      int32_t max_blocks, const int32_t* suffix_lens,
+                                      int32_t max_suffix_len, const void* suffix_k_pool,
+                                      const void* suffix_v_pool, const void* w_uk,
+                                      const void* w_uv, void* out, float* lse_out, void* stream);
 
 /*
  * Multi-level (tree-shaped) shared prefixes.  Section 3.1 ("Prefill") speaks of a tree-like query

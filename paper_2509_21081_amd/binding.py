@@ -13,8 +13,9 @@ import torch
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtyphoon_mla.so")
 
-TMLA_OK, TMLA_ERR_INVALID_ARG, TMLA_ERR_UNSUPPORTED, TMLA_ERR_WORKSPACE_TOO_SMALL, TMLA_ERR_HIP = \
-    range(5)
+(TMLA_OK, TMLA_ERR_INVALID_ARG, TMLA_ERR_UNSUPPORTED, TMLA_ERR_WORKSPACE_TOO_SMALL, TMLA_ERR_HIP,
+ TMLA_ERR_SCRATCH_LIMIT) = range(6)
+STATIC_SCRATCH_BYTES = 128 << 20
 MODE_MIXED, MODE_NAIVE_ONLY, MODE_ABSORB_ONLY, MODE_AUTO = 0, 1, 2, 3
 MODES = {"mixed": MODE_MIXED, "naive_only": MODE_NAIVE_ONLY, "absorb_only": MODE_ABSORB_ONLY,
          "auto": MODE_AUTO}
@@ -25,7 +26,7 @@ EXPORTS = [
     "typhoon_mla_expand_prefix", "typhoon_mla_expand_pool", "typhoon_mla_decode_workspace_bytes",
     "typhoon_mla_decode", "typhoon_mla_combine_lse", "typhoon_mla_set_debug_flags",
     "typhoon_mla_auto_batch_threshold", "typhoon_mla_decode_tree_workspace_bytes",
-    "typhoon_mla_decode_tree", "typhoon_mla_set_tuning",
+    "typhoon_mla_decode_tree", "typhoon_mla_set_tuning", "typhoon_mla_decode_static_scratch",
 ]
 TUNE_PREFIX_SPLITS, TUNE_SUFFIX_CHUNK, TUNE_ABSORB_PREFIX_CHUNK, TUNE_NAIVE_SUFFIX_CHUNK = range(4)
 
@@ -79,6 +80,11 @@ def lib():
             [P, c_int32, c_int32, c_int32, c_void_p, c_int32] + [c_void_p] * 4 +
             [c_void_p, c_int32, c_int32, c_void_p, c_int32, c_void_p, c_int32] +
             [c_void_p] * 4 + [c_void_p, c_void_p, c_void_p, c_size_t, c_void_p])
+        L.typhoon_mla_decode_static_scratch.restype = c_int
+        L.typhoon_mla_decode_static_scratch.argtypes = (
+            [P, c_int32, c_int32, c_int32, c_void_p, c_int32] + [c_void_p] * 4 +
+            [c_void_p, c_int32, c_int32, c_void_p, c_int32, c_void_p, c_int32] +
+            [c_void_p] * 4 + [c_void_p, c_void_p, c_void_p])
         L.typhoon_mla_combine_lse.restype = c_int
         L.typhoon_mla_combine_lse.argtypes = [c_int32, c_int64, c_int32, c_void_p, c_void_p,
                                               c_void_p, c_int32, c_void_p, c_void_p]
@@ -217,6 +223,27 @@ def typhoon_mla_decode(dims, mode, q, prefix_len, prefix_k=None, prefix_v=None, 
         _ptr(suffix_v_pool), _ptr(w_uk), _ptr(w_uv), _ptr(out), _ptr(lse_out), _ptr(workspace),
         workspace.numel(), _stream(dev))
     _check(st, "typhoon_mla_decode")
+    return out, lse_out
+
+
+def typhoon_mla_decode_static_scratch(dims, mode, q, prefix_len, out, lse_out=None, prefix_k=None,
+                                      prefix_v=None, prefix_ckv=None, prefix_krope=None,
+                                      suffix_pool=None, block_table=None, suffix_lens=None,
+                                      max_suffix_len=0, suffix_k_pool=None, suffix_v_pool=None,
+                                      w_uk=None, w_uv=None):
+    """typhoon_mla_decode on the library's static scratch array: nothing is allocated here or in
+    the library, so `out` (and `lse_out`, if wanted) are the caller's."""
+    mode = MODES[mode] if isinstance(mode, str) else int(mode)
+    B, S_q, H, _ = q.shape
+    num_blocks = suffix_pool.shape[0] if suffix_pool is not None else 0
+    block_size = suffix_pool.shape[1] if suffix_pool is not None else 64
+    max_blocks = block_table.shape[1] if block_table is not None else 0
+    st = lib().typhoon_mla_decode_static_scratch(
+        ctypes.byref(dims), mode, B, S_q, _ptr(q), prefix_len, _ptr(prefix_k), _ptr(prefix_v),
+        _ptr(prefix_ckv), _ptr(prefix_krope), _ptr(suffix_pool), num_blocks, block_size,
+        _ptr(block_table), max_blocks, _ptr(suffix_lens), max_suffix_len, _ptr(suffix_k_pool),
+        _ptr(suffix_v_pool), _ptr(w_uk), _ptr(w_uv), _ptr(out), _ptr(lse_out), _stream(q.device))
+    _check(st, "typhoon_mla_decode_static_scratch")
     return out, lse_out
 
 

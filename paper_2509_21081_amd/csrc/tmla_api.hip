@@ -4,6 +4,7 @@
 #include <atomic>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "tmla_common.hpp"
@@ -154,6 +155,8 @@ const char* typhoon_mla_status_string(int status) {
     case TMLA_ERR_UNSUPPORTED: return "unsupported dimensions, head count, block size or dtype";
     case TMLA_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
     case TMLA_ERR_HIP: return "HIP launch error";
+    case TMLA_ERR_SCRATCH_LIMIT:
+      return "the call needs more scratch memory than the library's static buffer holds";
     default: return "unknown status";
   }
 }
@@ -270,14 +273,22 @@ size_t typhoon_mla_decode_workspace_bytes(const tmla_dims* dims, int32_t mode, i
   return std::max(a, p.total);
 }
 
-int typhoon_mla_decode(const tmla_dims* dims, int32_t mode, int32_t batch, int32_t q_len,
+// Where the scratch memory of a decode call comes from: the caller's workspace, or the library's
+// static device array (then `get` is called after validation, with the bytes the plan needs).
+struct ScratchSource {
+  void* workspace;
+  size_t workspace_bytes;
+  int (*get)(size_t need, void** ptr);   // nullptr: use workspace / workspace_bytes
+};
+
+static int decode_impl(const tmla_dims* dims, int32_t mode, int32_t batch, int32_t q_len,
                        const void* q, int32_t prefix_len, const void* prefix_k,
                        const void* prefix_v, const void* prefix_ckv, const void* prefix_krope,
                        const void* suffix_pool, int32_t num_blocks, int32_t block_size,
                        const int32_t* block_table, int32_t max_blocks, const int32_t* suffix_lens,
                        int32_t max_suffix_len, const void* suffix_k_pool,
                        const void* suffix_v_pool, const void* w_uk, const void* w_uv, void* out,
-                       float* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
+                       float* lse_out, const ScratchSource& scratch_src, void* stream) {
   int st = check_decode_sizes(dims, mode, batch, q_len, prefix_len, max_suffix_len);
   if (st != TMLA_OK) return st;
   if (block_size != 64 && block_size != 128) return TMLA_ERR_UNSUPPORTED;
@@ -310,8 +321,13 @@ int typhoon_mla_decode(const tmla_dims* dims, int32_t mode, int32_t batch, int32
 
   Plan p;
   make_plan(dims, mode, batch, q_len, prefix_len, max_suffix_len, block_size, &p);
-  if (!workspace || misaligned(workspace, 256)) return TMLA_ERR_INVALID_ARG;
-  if (workspace_bytes < p.total) return TMLA_ERR_WORKSPACE_TOO_SMALL;
+  void* workspace = scratch_src.workspace;
+  if (scratch_src.get) {
+    if ((st = scratch_src.get(p.total, &workspace)) != TMLA_OK) return st;
+  } else {
+    if (!workspace || misaligned(workspace, 256)) return TMLA_ERR_INVALID_ARG;
+    if (scratch_src.workspace_bytes < p.total) return TMLA_ERR_WORKSPACE_TOO_SMALL;
+  }
 
   DecodeArgs a;
   a.q = q; a.prefix_k = prefix_k; a.prefix_v = prefix_v; a.prefix_ckv = prefix_ckv;
@@ -359,6 +375,59 @@ int typhoon_mla_decode(const tmla_dims* dims, int32_t mode, int32_t batch, int32
     }
   }
   return launches.status();
+}
+
+int typhoon_mla_decode(const tmla_dims* dims, int32_t mode, int32_t batch, int32_t q_len,
+                       const void* q, int32_t prefix_len, const void* prefix_k,
+                       const void* prefix_v, const void* prefix_ckv, const void* prefix_krope,
+                       const void* suffix_pool, int32_t num_blocks, int32_t block_size,
+                       const int32_t* block_table, int32_t max_blocks, const int32_t* suffix_lens,
+                       int32_t max_suffix_len, const void* suffix_k_pool,
+                       const void* suffix_v_pool, const void* w_uk, const void* w_uv, void* out,
+                       float* lse_out, void* workspace, size_t workspace_bytes, void* stream) {
+  const ScratchSource src = {workspace, workspace_bytes, nullptr};
+  return decode_impl(dims, mode, batch, q_len, q, prefix_len, prefix_k, prefix_v, prefix_ckv,
+                     prefix_krope, suffix_pool, num_blocks, block_size, block_table, max_blocks,
+                     suffix_lens, max_suffix_len, suffix_k_pool, suffix_v_pool, w_uk, w_uv, out,
+                     lse_out, src, stream);
+}
+
+// ---- decode on the library's own static scratch (for callers that cannot allocate) -----------
+// One array per GPU the library's code is loaded on, held until the process ends.  In host code
+// the array's name is only a handle for hipGetSymbolAddress; the device address it yields (per
+// device) is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[TMLA_STATIC_SCRATCH_BYTES];
+
+static constexpr int MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[MAX_DEVICES] = {};
+
+static int static_scratch(size_t need, void** ptr) {
+  if (need > (size_t)TMLA_STATIC_SCRATCH_BYTES) return TMLA_ERR_SCRATCH_LIMIT;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return TMLA_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return TMLA_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return TMLA_OK;
+}
+
+int typhoon_mla_decode_static_scratch(
+    const tmla_dims* dims, int32_t mode, int32_t batch, int32_t q_len, const void* q,
+    int32_t prefix_len, const void* prefix_k, const void* prefix_v, const void* prefix_ckv,
+    const void* prefix_krope, const void* suffix_pool, int32_t num_blocks, int32_t block_size,
+    const int32_t* block_table, int32_t max_blocks, const int32_t* suffix_lens,
+    int32_t max_suffix_len, const void* suffix_k_pool, const void* suffix_v_pool, const void* w_uk,
+    const void* w_uv, void* out, float* lse_out, void* stream) {
+  const ScratchSource src = {nullptr, 0, static_scratch};
+  return decode_impl(dims, mode, batch, q_len, q, prefix_len, prefix_k, prefix_v, prefix_ckv,
+                     prefix_krope, suffix_pool, num_blocks, block_size, block_table, max_blocks,
+                     suffix_lens, max_suffix_len, suffix_k_pool, suffix_v_pool, w_uk, w_uv, out,
+                     lse_out, src, stream);
 }
 
 // ---- tree-shaped shared prefixes -----------------------------------------------------------

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_status_strings():
     assert T.typhoon_mla_status_string(0) == "ok"
-    for s in range(1, 5):
+    for s in range(1, 6):
         assert T.typhoon_mla_status_string(s) not in ("ok", "unknown status")
     assert T.typhoon_mla_status_string(99) == "unknown status"
 
@@ -138,6 +138,38 @@ def test_tuning_overrides_change_the_plan_and_are_restored():
     finally:
         T.typhoon_mla_set_tuning(T.TUNE_SUFFIX_CHUNK, old)
     assert T.typhoon_mla_decode_workspace_bytes(d, T.MODE_MIXED, 64, 1, 4096, 2048) == base
+
+
+def test_static_scratch_decode_validates_before_touching_the_gpu():
+    """Same argument checks as typhoon_mla_decode, and a clear error for a problem whose
+    intermediates do not fit the static array -- all on the host, nothing launched."""
+    L = T.lib()
+    P = ctypes.byref
+    p4k = ctypes.c_void_p(4096)
+
+    def call(d, batch=4, mode=0, q=p4k, prefix_len=256, max_suffix=100, max_blocks=2,
+             block_size=64, num_blocks=9):
+        return L.typhoon_mla_decode_static_scratch(
+            P(d), mode, batch, 1, q, prefix_len, p4k, p4k, p4k, p4k, p4k, num_blocks, block_size,
+            p4k, max_blocks, p4k, max_suffix, None, None, p4k, p4k, p4k, None, None)
+    d = _dims(num_heads=128)
+    assert call(d, q=None) == T.TMLA_ERR_INVALID_ARG
+    assert call(d, mode=7) == T.TMLA_ERR_INVALID_ARG
+    assert call(d, block_size=48) == T.TMLA_ERR_UNSUPPORTED
+    assert call(d, max_suffix=200) == T.TMLA_ERR_INVALID_ARG            # 2*64 < 200
+    assert call(d, batch=0) == T.TMLA_OK
+    assert T.typhoon_mla_decode_workspace_bytes(d, 0, 2048, 1, 4096, 4096) > T.STATIC_SCRATCH_BYTES
+    assert call(d, batch=2048, prefix_len=4096, max_suffix=4096, max_blocks=64) == \
+        T.TMLA_ERR_SCRATCH_LIMIT
+    assert "static" in T.typhoon_mla_status_string(T.TMLA_ERR_SCRATCH_LIMIT)
+    header = open(os.path.join(ROOT, "include", "typhoon_mla.h")).read()
+    assert "#define TMLA_STATIC_SCRATCH_BYTES (128u << 20)" in header
+    # the benchmark configurations all fit
+    for B, S, H, Ls, Ln in [(64, 1, 128, 4096, 512), (256, 1, 128, 32768, 2048),
+                            (128, 2, 128, 8192, 1024), (512, 1, 16, 16384, 4096)]:
+        dd = _dims(num_heads=H)
+        for m in (T.MODE_MIXED, T.MODE_ABSORB_ONLY, T.MODE_NAIVE_ONLY):
+            assert T.typhoon_mla_decode_workspace_bytes(dd, m, B, S, Ls, Ln) <= T.STATIC_SCRATCH_BYTES
 
 
 def test_combine_validation():
