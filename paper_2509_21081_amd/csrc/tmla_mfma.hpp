@@ -104,23 +104,25 @@ __device__ __forceinline__ float softmax_block(f32x16& s, float& m, float& l, fl
 
 // Same contract as softmax_block, for blocks known to be full (no masking), with a shortcut for
 // the common case that the exponent reference is still good: the probabilities are formed
-// against the current reference straight away, and their per-lane sum -- taken by the bf16 dot
-// instruction from the packed values the second product will use -- doubles as the range check:
-// no probability can exceed a sum that stays below 2^(RESCALE_TAU + 4).  Then neither the block
-// maximum nor the exchange between the lane halves is needed.  Otherwise (first block, or a
-// score far above the reference) the scores are still intact and the full update runs.
+// against the current reference straight away, and their per-lane sum doubles as the range
+// check: no probability can exceed a sum that stays below 2^(RESCALE_TAU + 4).  Then neither the
+// block maximum nor the exchange between the lane halves is needed.  Otherwise (first block, or
+// a score far above the reference) the scores are still intact and the full update runs.  The
+// sum is taken over the unrounded exponentials: the bf16 rounding of a dominant probability
+// (relative 2^-9) would otherwise go straight into the denominator and the LSE.
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 __device__ inline float softmax_block_fast(f32x16& s, float& m, float& l, float c, int g,
                                            bf16x8& p0, bf16x8& p1, bool& rescale) {
   bf16x8 q0, q1;
-#pragma unroll
-  for (int v = 0; v < 8; v++) {
-    q0[v] = (__bf16)fast_exp2(__builtin_fmaf(s[v], c, -m));       // m = -inf gives inf: falls through
-    q1[v] = (__bf16)fast_exp2(__builtin_fmaf(s[8 + v], c, -m));
-  }
   float sum = 0.f;
 #pragma unroll
-  for (int v = 0; v < 8; v++) sum += (float)q0[v] + (float)q1[v];
+  for (int v = 0; v < 8; v++) {
+    const float e0 = fast_exp2(__builtin_fmaf(s[v], c, -m));       // m = -inf gives inf: falls through
+    const float e1 = fast_exp2(__builtin_fmaf(s[8 + v], c, -m));
+    sum += e0 + e1;
+    q0[v] = (__bf16)e0;
+    q1[v] = (__bf16)e1;
+  }
   const bool good = sum <= 16.f * 256.f;   // 2^(RESCALE_TAU + 4); false for inf and NaN
   if (__builtin_amdgcn_ballot_w64(!good) == 0) {
     l += sum;

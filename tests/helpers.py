@@ -7,8 +7,72 @@ from paper_2509_21081_amd import binding as T
 # Tolerances: bf16 I/O with fp32 accumulation -> max-abs 1e-2 + max-rel 2e-2 element-wise, plus a
 # row-wise relative L2 bound and an LSE bound so that small outputs cannot hide an error;
 # fp32 mode -> 1e-4 for all three.
+#
+# Peaked softmax rows (queries scaled by a gain g, or one part of the keys scaled up): bf16
+# storage alone -- the expanded keys of the prefix and the absorbed query of the suffix, both
+# mandated by bf16 I/O -- perturbs a logit by sigma_x = 3.9e-4 g (relative rounding 2^-9 / sqrt 3 on
+# each of 128 products q_i k_i).  In a near-uniform softmax these errors average out (LSE error
+# 1.1e-5 simulated at g = 1); in a peaked row the LSE moves by the error of the top logit and the
+# output by |do| <= dx * sum_t p_t |v_t - o|.  Simulated in fp64 with only those two roundings
+# on the B = 64, H = 128 configuration at g = 8: LSE error sigma 3.1e-3, maximum 1.6e-2 = 5.1
+# sigma over 2048 rows; the per-row sigma varies with the query's size, so over the 10^4 .. 10^5
+# rows of a full configuration the maximum reaches 6 sigma.  Bounds for peaked rows:
+#   LSE      8 sigma_x                         = 3.2e-3 g
+#   output   8 sigma_x * 0.8 (sum p |v - o| <= 1.8 sigma_v, sigma_v = 0.45), never below the
+#            unscaled bound                    = max(1e-2, 2.5e-3 g) absolute, + 2e-2 relative
+#   row L2   the same error against a row norm of about |v_top| = sigma_v sqrt(128):
+#            max(2e-2, 5e-3 g)
 TOL = {"bf16": dict(atol=1e-2, rtol=2e-2, row_l2=2e-2, lse=2e-3),
        "fp32": dict(atol=1e-4, rtol=1e-4, row_l2=1e-4, lse=1e-4)}
+
+
+def _worker_count():
+    import os
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n = os.cpu_count() or 1
+    return max(1, min(16, n))
+
+
+def _merge_nan(parts, like):
+    out = np.full_like(like[0], np.nan), np.full_like(like[1], np.nan)
+    for o, l in parts:
+        m = ~np.isnan(l)
+        out[0][m] = o[m]
+        out[1][m] = l[m]
+    return out
+
+
+def oracle_definition_parallel(O, a, pairs, workers=None):
+    """O.mla_decode_definition on `pairs`, the heads dealt out to a pool of threads (numpy's
+    kernels release the interpreter lock).  A head stays within one thread, so its prefix
+    expansion is still formed once.  The oracle itself is called as it stands."""
+    from concurrent.futures import ThreadPoolExecutor
+    from threadpoolctl import threadpool_limits
+    workers = workers or _worker_count()
+    heads = sorted({h for _, h in pairs})
+    groups = [[p for p in pairs if p[1] in set(heads[w::workers])] for w in range(workers)]
+    groups = [g for g in groups if g]
+    with threadpool_limits(limits=1):
+        with ThreadPoolExecutor(len(groups)) as ex:
+            parts = list(ex.map(lambda g: O.mla_decode_definition(**a, pairs=g), groups))
+    return _merge_nan(parts, parts[0])
+
+
+def oracle_absorb_all_heads_parallel(O, a, requests=None, workers=None):
+    """O.mla_decode_absorb_all_heads over `requests` (default: all), the requests dealt out to a
+    pool of threads."""
+    from concurrent.futures import ThreadPoolExecutor
+    from threadpoolctl import threadpool_limits
+    workers = workers or _worker_count()
+    reqs = list(range(a["q"].shape[0])) if requests is None else list(requests)
+    groups = [reqs[w::workers] for w in range(workers)]
+    groups = [g for g in groups if g]
+    with threadpool_limits(limits=1):
+        with ThreadPoolExecutor(len(groups)) as ex:
+            parts = list(ex.map(lambda g: O.mla_decode_absorb_all_heads(**a, requests=g), groups))
+    return _merge_nan(parts, parts[0])
 
 
 def dims_of(wl):
@@ -38,15 +102,20 @@ def run_library(wl, mode, device, expanded=None, flags=0):
     return out.double().cpu().numpy(), lse.double().cpu().numpy()
 
 
-def assert_parity(got, got_lse, ref, ref_lse, dtype, what="", logit_gain=1.0):
+def assert_parity(got, got_lse, ref, ref_lse, dtype, what="", logit_gain=1.0, peaked=None):
     """Element-wise, row-wise and LSE comparison wherever the reference was computed (not NaN).
 
-    `logit_gain`: factor by which the queries (hence the logits) were scaled up; the bf16
-    rounding of the expanded keys and of the absorbed query perturbs a logit in proportion to
-    its magnitude, so the LSE bound scales with it (the output bounds do not)."""
+    `logit_gain`: factor by which the queries (hence the logits) were scaled up; `peaked`: the
+    softmax rows are dominated by few tokens (default: logit_gain > 1).  For peaked rows the
+    bounds follow the rounding of the stored operands as derived at the top of this file."""
     tol = dict(TOL[dtype])
-    if dtype == "bf16":
-        tol["lse"] *= max(1.0, logit_gain)
+    if peaked is None:
+        peaked = logit_gain > 1.0
+    if dtype == "bf16" and peaked:
+        g = max(1.0, logit_gain)
+        tol["lse"] = 3.2e-3 * g
+        tol["atol"] = max(tol["atol"], 2.5e-3 * g)
+        tol["row_l2"] = max(tol["row_l2"], 5e-3 * g)
     mask = ~np.isnan(ref_lse)
     assert mask.any(), "reference is empty"
     g, r = got[mask], ref[mask]
