@@ -51,6 +51,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stages", action="store_true")
     ap.add_argument("--sweep", action="store_true")
+    ap.add_argument("--sweep-heads", default="128,64")
+    ap.add_argument("--sweep-batches", default="1,2,4,8,16,32,64,128,256,512,1024")
+    ap.add_argument("--sweep-prefix", type=int, default=4096)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference for HBM counters)")
     ap.add_argument("--cpu-sample-requests", type=int, default=0,
@@ -442,18 +445,24 @@ def bench_sweep(args, torch, T, C, W, dev):
     figure) for DeepSeek-v3 (128 heads) and Kimi K2 (64 heads): mixed / absorb_only / auto step
     times and the per-kernel breakdown of the mixed step."""
     rows = []
-    for H in (128, 64):
-        for B in (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024):
-            name = "B=%d,H=%d,Ls=4096,Ln=512" % (B, H)
+    Ls = args.sweep_prefix
+    for H in [int(x) for x in args.sweep_heads.split(",")]:
+        for B in [int(x) for x in args.sweep_batches.split(",")]:
+            name = "B=%d,H=%d,Ls=%d,Ln=512" % (B, H, Ls)
             case = Case(spec_of(name, W), ["mixed", "absorb_only", "auto"], torch, T, C, W, dev)
-            steps = 30 if B <= 256 else 15
-            ms = {m: event_time(lambda: case.step(m), steps, 5, torch)
-                  for m in ("mixed", "absorb_only", "auto")}
-            st = stage_times_in_step(lambda: case.step("mixed"), T, torch, 5, 4096)
-            row = {"heads": H, "batch": B, "ms_mixed": ms["mixed"], "ms_absorb_only": ms["absorb_only"],
+            steps = 20 if B <= 256 else 10
+            # the clock moves with what ran just before: the modes take turns and the median of
+            # the rounds is kept
+            rounds = {m: [] for m in ("mixed", "absorb_only", "auto")}
+            for _ in range(5):
+                for m in rounds:
+                    rounds[m].append(event_time(lambda: case.step(m), steps, 2, torch))
+            ms = {m: sorted(v)[len(v) // 2] for m, v in rounds.items()}
+            st = stage_times_in_step(lambda: case.step("mixed"), T, torch, 5, Ls)
+            row = {"heads": H, "batch": B, "prefix_len": Ls, "ms_mixed": ms["mixed"], "ms_absorb_only": ms["absorb_only"],
                    "ms_auto": ms["auto"], "speedup_vs_absorb_only": ms["absorb_only"] / ms["mixed"],
                    "auto_vs_best": ms["auto"] / min(ms["mixed"], ms["absorb_only"]),
-                   "auto_threshold": T.typhoon_mla_auto_batch_threshold(1), "kernel_ms": st}
+                   "auto_threshold": T.typhoon_mla_auto_batch_threshold(case.dims, 1, Ls), "kernel_ms": st}
             rows.append(row)
             print(json.dumps(row), flush=True)
             del case

@@ -111,15 +111,18 @@ int typhoon_mla_expand_pool(const tmla_dims* dims, int32_t num_blocks, int32_t b
                             void* suffix_k_pool, void* suffix_v_pool, void* stream);
 
 /*
- * Break-even batch size B_theta of Section 3.2, (D_qk + D_v) / (q_len (2 D_l + D_r)) * T / M, with
- * the throughput T of this library's absorb kernel over a shared prefix and the bandwidth M of its
- * naive prefix kernel as measured on MI355X at the small batches where the two meet (about
- * 100 TFLOP/s and 5 TB/s, giving 5.9 / q_len; the measured cross-over at prefix 4096 /
- * suffix 512 lies between batch 4 and 8).  The environment variable
- * TMLA_AUTO_BATCH_THRESHOLD, read once per process, overrides it.  TMLA_MODE_AUTO uses mixed
- * when batch >= this value.
+ * Break-even batch size of Section 3.2 ("Fall-back to Absorb" in Section 3.1): TMLA_MODE_AUTO
+ * runs mixed when batch >= this value and absorb_only below it.  The paper's closed form,
+ * B_theta = (D_qk + D_v) / (q_len (2 D_l + D_r)) * T / M, has the absorb throughput T as a
+ * constant; on MI355X a batch near the cross-over is too small to fill the chip, so the effective
+ * T depends on the heads per request and on the prefix length.  The library uses a fit to its own
+ * measured cross-overs (q_len = 1: 6 at 128 heads / prefix 4096, 28 at 128 / 16384, 7 at
+ * 64 / 16384, none -- mixed always wins -- at 16 heads):
+ *     B_theta = max(0, 7.3 (H / 128)^1.7 (prefix_len / 4096) - 1.5) / q_len.
+ * The environment variable TMLA_AUTO_BATCH_THRESHOLD, read once per process, overrides it.
+ * Returns -1 on invalid arguments.
  */
-double typhoon_mla_auto_batch_threshold(int32_t q_len);
+double typhoon_mla_auto_batch_threshold(const tmla_dims* dims, int32_t q_len, int32_t prefix_len);
 
 /* Scratch bytes typhoon_mla_decode needs for this problem size (a pure host function). */
 size_t typhoon_mla_decode_workspace_bytes(const tmla_dims* dims, int32_t mode, int32_t batch,

@@ -89,7 +89,7 @@ def lib():
         L.typhoon_mla_combine_lse.argtypes = [c_int32, c_int64, c_int32, c_void_p, c_void_p,
                                               c_void_p, c_int32, c_void_p, c_void_p]
         L.typhoon_mla_auto_batch_threshold.restype = ctypes.c_double
-        L.typhoon_mla_auto_batch_threshold.argtypes = [c_int32]
+        L.typhoon_mla_auto_batch_threshold.argtypes = [P, c_int32, c_int32]
         N = POINTER(tmla_prefix_node)
         L.typhoon_mla_decode_tree_workspace_bytes.restype = c_size_t
         L.typhoon_mla_decode_tree_workspace_bytes.argtypes = [P, c_int32, c_int32, N, c_int32,
@@ -145,8 +145,8 @@ def typhoon_mla_set_tuning(key, value):
     return old
 
 
-def typhoon_mla_auto_batch_threshold(q_len=1):
-    return lib().typhoon_mla_auto_batch_threshold(int(q_len))
+def typhoon_mla_auto_batch_threshold(dims, q_len=1, prefix_len=4096):
+    return lib().typhoon_mla_auto_batch_threshold(ctypes.byref(dims), int(q_len), int(prefix_len))
 
 
 def typhoon_mla_expanded_k_bytes(dims, num_tokens):

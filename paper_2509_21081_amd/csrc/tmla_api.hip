@@ -1,6 +1,7 @@
 // C ABI of the TyphoonMLA decode library: host-side argument validation, launch planning /
 // workspace layout, and dispatch to the kernels.  No HIP call is made before validation passes.
 #include <algorithm>
+#include <cmath>
 #include <atomic>
 #include <cstdlib>
 #include <cstring>
@@ -241,30 +242,38 @@ static int check_decode_sizes(const tmla_dims* dims, int mode, int batch, int q_
   return TMLA_OK;
 }
 
-// Measured on MI355X near the cross-over: absorb attention over a shared prefix delivers
-// ~100 TFLOP/s at the small batches in question (it reaches ~450 only with hundreds of query rows
-// per request), the naive prefix pass streams at ~5 TB/s.  The measured cross-over at
-// L_s = 4096, H = 128 lies between batch 4 and 8.
-static constexpr double AUTO_T_FLOPS = 100e12, AUTO_M_BYTES = 5e12;
-
-double typhoon_mla_auto_batch_threshold(int32_t q_len) {
-  if (tuning().auto_threshold >= 0.0) return tuning().auto_threshold;
-  if (q_len <= 0) q_len = 1;
-  // Section 3.2: L_s H (D_qk+D_v) w / M = B S_q L_s H (2 D_l + D_r) 2 / T  with w = 2 bytes
-  return (double)(D_QK + D_V) / (q_len * (2.0 * D_L + D_R)) * AUTO_T_FLOPS / AUTO_M_BYTES;
+// Section 3.2's break-even batch is B_theta = (D_qk + D_v) / (S_q (2 D_l + D_r)) * T / M.  On this
+// GPU the absorb throughput T over a shared prefix is not a constant near the cross-over: a small
+// batch cannot fill the chip (few requests, each cut into a bounded number of chunks), so the
+// effective T grows with the rows per request (heads) and with the prefix length, while the naive
+// pass streams at M ~ 5.5 TB/s throughout.  Measured cross-overs (bench.py --sweep; batch at which
+// mixed overtakes absorb_only, S_q = 1): 128 heads: 6 at L_s = 4096, 28 at 16384; 64 heads: below 1
+// at 4096, 7 at 16384; 16 heads: mixed wins at every batch.  The fit below reproduces them; in
+// the paper's form it is the closed formula with T_eff = M (2 D_l + D_r) / (D_qk + D_v) * B_theta.
+static double fitted_batch_threshold(int heads, int prefix_len) {
+  const double p = 7.3 * std::pow(heads / 128.0, 1.7);
+  return std::max(0.0, p * (prefix_len / 4096.0) - 1.5);
 }
 
-static int resolve_auto(int mode, int batch, int q_len, int prefix_len) {
+double typhoon_mla_auto_batch_threshold(const tmla_dims* dims, int32_t q_len, int32_t prefix_len) {
+  if (check_dims(dims) != TMLA_OK || prefix_len < 0) return -1.0;
+  if (tuning().auto_threshold >= 0.0) return tuning().auto_threshold;
+  if (q_len <= 0) q_len = 1;
+  return fitted_batch_threshold(dims->num_heads, prefix_len) / q_len;
+}
+
+static int resolve_auto(const tmla_dims* dims, int mode, int batch, int q_len, int prefix_len) {
   if (mode != TMLA_MODE_AUTO) return mode;
   if (prefix_len == 0) return TMLA_MODE_MIXED;   // nothing to choose: both run the absorb suffix
-  return batch >= typhoon_mla_auto_batch_threshold(q_len) ? TMLA_MODE_MIXED : TMLA_MODE_ABSORB_ONLY;
+  return batch >= typhoon_mla_auto_batch_threshold(dims, q_len, prefix_len) ? TMLA_MODE_MIXED
+                                                                           : TMLA_MODE_ABSORB_ONLY;
 }
 
 size_t typhoon_mla_decode_workspace_bytes(const tmla_dims* dims, int32_t mode, int32_t batch,
                                           int32_t q_len, int32_t prefix_len,
                                           int32_t max_suffix_len) {
   if (check_decode_sizes(dims, mode, batch, q_len, prefix_len, max_suffix_len) != TMLA_OK) return 0;
-  mode = resolve_auto(mode, batch, q_len, prefix_len);
+  mode = resolve_auto(dims, mode, batch, q_len, prefix_len);
   Plan p;
   // the plan rounds suffix chunks to the paged block size; 128 covers both supported sizes
   make_plan(dims, mode, batch, q_len, prefix_len, max_suffix_len, 128, &p);
@@ -299,7 +308,7 @@ static int decode_impl(const tmla_dims* dims, int32_t mode, int32_t batch, int32
   if (mode == TMLA_MODE_AUTO) {
     if (prefix_len > 0 && (!prefix_k || !prefix_v || !prefix_ckv || !prefix_krope))
       return TMLA_ERR_INVALID_ARG;
-    mode = resolve_auto(mode, batch, q_len, prefix_len);
+    mode = resolve_auto(dims, mode, batch, q_len, prefix_len);
   }
   const bool need_naive_prefix = prefix_len > 0 && mode != TMLA_MODE_ABSORB_ONLY;
   const bool need_latent_prefix = prefix_len > 0 && mode == TMLA_MODE_ABSORB_ONLY;

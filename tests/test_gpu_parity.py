@@ -331,13 +331,31 @@ def test_modes_agree_with_each_other(gpu_device):
         np.testing.assert_allclose(outs[m][1][fin], outs["mixed"][1][fin], atol=2e-3)
 
 
-@pytest.mark.parametrize("case", ["ragged_h16", "wide_batch"])
+AUTO_CASES = {
+    # below the break-even batch of 128 heads and a 2048-token prefix (2.2): absorb_only runs
+    "below_break_even": dict(batch=2, heads=128, q_len=1, prefix_len=2048, suffix_min=10,
+                             suffix_max=120, seed=51),
+    # above it: mixed runs
+    "above_break_even": dict(batch=5, heads=128, q_len=1, prefix_len=2048, suffix_min=0,
+                             suffix_max=120, seed=52),
+    # 16 heads: the naive prefix pass wins at every batch
+    "h16": dict(batch=3, heads=16, q_len=1, prefix_len=100, suffix_min=0, suffix_max=150, seed=11),
+}
+
+
+@pytest.mark.parametrize("case", list(AUTO_CASES))
 def test_auto_mode_matches_oracle(case, gpu_device):
-    # batch 3 is below the break-even batch (absorb_only is chosen), batch 70 above it (mixed)
-    wl, (ref, ref_lse) = _workload_and_ref(case, "bf16")
-    print(f"auto mode case={case}", flush=True)
+    wl = W.make_workload(W.small_spec(name=case, dtype="bf16", **AUTO_CASES[case]))
+    spec = wl.spec
+    thr = T.typhoon_mla_auto_batch_threshold(Hh.dims_of(wl), spec.q_len, spec.prefix_len)
+    assert (spec.batch < thr) == (case == "below_break_even")
+    ref, ref_lse = O.mla_decode_definition(**wl.as_float64())
+    print(f"auto mode case={case} threshold={thr:.2f}", flush=True)
     got, got_lse = Hh.run_library(wl, "auto", gpu_device)
     Hh.assert_parity(got, got_lse, ref, ref_lse, "bf16", f"{case}/auto")
+    # auto is exactly the mode it resolves to
+    same, same_lse = Hh.run_library(wl, "absorb_only" if spec.batch < thr else "mixed", gpu_device)
+    assert np.array_equal(got, same) and np.array_equal(got_lse, same_lse)
 
 
 @pytest.mark.parametrize("case,flags", [("h128_many_tiles", 0), ("ragged_h16", 0),
