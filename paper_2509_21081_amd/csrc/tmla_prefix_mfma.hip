@@ -375,18 +375,26 @@ __device__ inline void pl_mfma_s(f32x16& d, const bf16x8& a, const bf16x8& b) {
 __device__ inline void pl_mfma_o(f32x16& d, const bf16x8& a, const bf16x8& b) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b));
 }
-// the same, behind a wait for the oldest outstanding fragment read (operand a)
+// The same, behind a wait for outstanding fragment reads.  The reads return in order and one is
+// issued per quantum, PL_D quanta ahead of its use; waiting once per PL_WG quanta until at most
+// PL_D - PL_WG of them are in flight makes the fragments of the whole group valid (a wait costs
+// a lone wavefront an issue slot like any other instruction).
+#ifndef PL_WG
+#define PL_WG 4
+#endif
+constexpr int PL_WAIT = PL_D - PL_WG;
+static_assert(PL_WAIT >= 0 && 20 % PL_WG == 0, "a period's 20 quanta are waited for in whole groups");
 __device__ inline void pl_mfma_s_first_w(f32x16& d, const bf16x8& a, const bf16x8& b) {
   asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0"
-               : "=&v"(d) : "v"(a), "a"(b), "n"(PL_D - 1));
+               : "=&v"(d) : "v"(a), "a"(b), "n"(PL_WAIT));
 }
 __device__ inline void pl_mfma_s_w(f32x16& d, const bf16x8& a, const bf16x8& b) {
   asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
-               : "+v"(d) : "v"(a), "a"(b), "n"(PL_D - 1));
+               : "+v"(d) : "v"(a), "a"(b), "n"(PL_WAIT));
 }
 __device__ inline void pl_mfma_o_w(f32x16& d, const bf16x8& a, const bf16x8& b) {
   asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
-               : "+a"(d) : "v"(a), "v"(b), "n"(PL_D - 1));
+               : "+a"(d) : "v"(a), "v"(b), "n"(PL_WAIT));
 }
 // enough idle issue slots for the last MFMA (16 passes) to have written its result
 __device__ inline void pl_mfma_drain() {
@@ -571,16 +579,17 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
       constexpr int cur = (4 * PAR + j) % 8;
       static_for<2>([&](auto nb_tag) {
         constexpr int nb = decltype(nb_tag)::value;
-        // (the first MFMA waits for fragment j: PL_D - 1 younger requests may be in flight)
+        // (the first MFMA of a group of PL_WG quanta waits for the group's fragments)
+        constexpr bool wait_here = nb == 0 && j % PL_WG == 0;
         if constexpr (j == 0) {
-          if constexpr (nb == 0) pl_mfma_s_first_w(s_out[nb], fr[cur], qf[nb][j]);
+          if constexpr (wait_here) pl_mfma_s_first_w(s_out[nb], fr[cur], qf[nb][j]);
           else pl_mfma_s_first(s_out[nb], fr[cur], qf[nb][j]);
         } else if constexpr (j < 12) {
-          if constexpr (nb == 0) pl_mfma_s_w(s_out[nb], fr[cur], qf[nb][j]);
+          if constexpr (wait_here) pl_mfma_s_w(s_out[nb], fr[cur], qf[nb][j]);
           else pl_mfma_s(s_out[nb], fr[cur], qf[nb][j]);
         } else {
           constexpr int kk = (j - 12) / 4, db = (j - 12) % 4;
-          if constexpr (nb == 0) pl_mfma_o_w(o[db][nb], fr[cur], p_in[nb][kk]);
+          if constexpr (wait_here) pl_mfma_o_w(o[db][nb], fr[cur], p_in[nb][kk]);
           else pl_mfma_o(o[db][nb], fr[cur], p_in[nb][kk]);
         }
         PL_SB();
@@ -600,8 +609,14 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
       });
     });
     // Control flow joins below and at the top of the next period, and register copies may be
-    // placed there; the last MFMAs must have written their results before any such copy.
-    pl_mfma_drain();
+    // placed there; the last MFMAs must have written their results before any such copy.  The
+    // steady-state periods follow each other without a join, and nothing reads this period's
+    // last results before the next period is well under way (the generated code is checked for
+    // that, across the loop's back edge as well).
+#ifndef PL_STEADY_DRAIN
+    if constexpr (!STEADY)
+#endif
+      pl_mfma_drain();
     if (STEADY || t < nfull) {
       l[0] += sum[0];
       l[1] += sum[1];
