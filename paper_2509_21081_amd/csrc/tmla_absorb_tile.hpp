@@ -110,10 +110,10 @@ __device__ __attribute__((always_inline)) inline void issue_part(const RowSrc& s
   if constexpr (K < 8) {
     const int r = d.wave + 4 * K;          // (r >> 2) & 3 == K & 3
     const int rr = min(r, s.last);
-    dma16(s.lat + (size_t)rr * s.lat_stride + d.off[K & 3], dst + r * AB_ROW_BYTES);
+    dma16_stream(s.lat + (size_t)rr * s.lat_stride + d.off[K & 3], dst + r * AB_ROW_BYTES);
   } else {
     const int rr = min(d.rope_row, s.last);
-    dma16(s.rope + (size_t)rr * s.rope_stride + d.rope_ch, dst + AB_MAIN_BYTES + d.wave * 1024);
+    dma16_stream(s.rope + (size_t)rr * s.rope_stride + d.rope_ch, dst + AB_MAIN_BYTES + d.wave * 1024);
   }
 }
 __device__ __attribute__((always_inline)) inline void issue_all(const RowSrc& s, char* dst,

@@ -161,15 +161,15 @@ __global__ void __launch_bounds__(512 / NB, 1) prefix_attn_query_split_kernel(Pr
     if (k_mover) {
       const char* s0 = ksrc + (size_t)i * (K_BLK_ELEMS * 2);
       char* dst = slot + wq * 1024;
-      dma16(s0, dst);
-      dma16(s0 + 4096, dst + 4096);
-      dma16(s0 + 8192, dst + 8192);
+      dma16_stream(s0, dst);
+      dma16_stream(s0 + 4096, dst + 4096);
+      dma16_stream(s0 + 8192, dst + 8192);
     }
     if (v_mover) {
       const char* s0 = vsrc + (size_t)i * (V_BLK_ELEMS * 2);
       char* dst = slot + K_BLK_ELEMS * 2 + wq * 1024;
-      dma16(s0, dst);
-      dma16(s0 + 4096, dst + 4096);
+      dma16_stream(s0, dst);
+      dma16_stream(s0 + 4096, dst + 4096);
     }
   };
 #pragma unroll
@@ -396,6 +396,28 @@ __device__ inline void pl_mfma_o_w(f32x16& d, const bf16x8& a, const bf16x8& b) 
   asm volatile("s_waitcnt lgkmcnt(%3)\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
                : "+a"(d) : "v"(a), "v"(b), "n"(PL_WAIT));
 }
+// An output MFMA with one global -> LDS transfer behind it.  M0 (the transfer's LDS address) is
+// set in front of the MFMA, which then fills the wait state the hardware wants between a write
+// of M0 and its use; set next to the transfer it costs an idle issue slot.  Same contract as
+// dma16_scalar_base: wave-uniform base and LDS address, 32-bit per-lane offset.
+template <bool WAIT>
+__device__ inline void pl_mfma_o_dma(f32x16& d, const bf16x8& a, const bf16x8& b,
+                                     uint32_t lane_off, const void* base, uint32_t lds) {
+  const uint64_t u = (uint64_t)base;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+  base = (const void*)(((uint64_t)hi << 32) | lo);
+  lds = __builtin_amdgcn_readfirstlane(lds);
+  if constexpr (WAIT)
+    asm volatile("s_mov_b32 m0, %5\n\ts_waitcnt lgkmcnt(%6)\n\t"
+                 "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\tglobal_load_lds_dwordx4 %3, %4" TMLA_STREAM_POLICY
+                 : "+a"(d) : "v"(a), "v"(b), "v"(lane_off), "s"(base), "s"(lds), "n"(PL_WAIT)
+                 : "memory");
+  else
+    asm volatile("s_mov_b32 m0, %5\n\t"
+                 "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\tglobal_load_lds_dwordx4 %3, %4" TMLA_STREAM_POLICY
+                 : "+a"(d) : "v"(a), "v"(b), "v"(lane_off), "s"(base), "s"(lds) : "memory");
+}
 // enough idle issue slots for the last MFMA (16 passes) to have written its result
 __device__ inline void pl_mfma_drain() {
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");
@@ -436,8 +458,13 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
                      "+a"(qf[nb][ks + 3])::"memory");
 
   // transfers: fragment f of a block is moved by wavefront f % 4 (K: 12 fragments, V: 8)
-  const char* kbase = (const char*)(a.pk + ((size_t)h * a.ntb + tb0) * K_BLK_ELEMS);
-  const char* vbase = (const char*)(a.pv + ((size_t)h * a.ntb + tb0) * V_BLK_ELEMS);
+#ifdef PL_PROBE_ALIAS   // timing probe only (wrong results): every head reads the cache of head h % PL_PROBE_ALIAS
+  const int hk = h % PL_PROBE_ALIAS;
+#else
+  const int hk = h;
+#endif
+  const char* kbase = (const char*)(a.pk + ((size_t)hk * a.ntb + tb0) * K_BLK_ELEMS);
+  const char* vbase = (const char*)(a.pv + ((size_t)hk * a.ntb + tb0) * V_BLK_ELEMS);
   const uint32_t lds_base = lds_addr(smem) + wave * 1024;
   uint32_t lane_off[3];   // fragment w, w + 4, w + 8 of a block
 #pragma unroll
@@ -510,6 +537,15 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
     bf16x8 (&p_in)[2][2] = pb[PAR ^ 1];
 
     sync(t, steady_tag);
+#ifdef PL_PROBE_NOMATH   // timing probe only (wrong results): the stream without the arithmetic
+    if constexpr (STEADY) {
+      const int kgp = t + PL_AHEAD;
+      dma_k(kgp, 0, NOGUARD{}); dma_k(kgp, 1, NOGUARD{}); dma_k(kgp, 2, NOGUARD{});
+      dma_v(kgp - 3, 0, NOGUARD{}); dma_v(kgp - 3, 1, NOGUARD{});
+      if (PL_PROBE_NOMATH > 0) __builtin_amdgcn_s_sleep(PL_PROBE_NOMATH);
+      return;
+    }
+#endif
     const uint32_t ka1 = lane_addr + ((t + 1) & (PL_NK - 1)) * PL_K_BYTES;   // K(t+1)
     const uint32_t ka2 = lane_addr + ((t + 2) & (PL_NK - 1)) * PL_K_BYTES;   // K(t+2)
     const uint32_t va =                                                // V(t-1), or K(0)
@@ -517,7 +553,10 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
     const int kg = t + PL_AHEAD;      // group issued in this period
 
     float xa = 0.f, xb = 0.f, ea = 0.f, eb = 0.f;
-    float sum[2] = {0.f, 0.f};   // denominators of block t, per column block
+    // denominators of block t, per column block; the two probabilities of a packed pair go to
+    // separate sums (a temporary for their sum lands in the register next to the packed pair,
+    // and the write behind the conversion then costs a wait state)
+    float sum[2] = {0.f, 0.f}, sum_b[2] = {0.f, 0.f};
     // The softmax of block t, two scores (one packed pair of probabilities) per quantum, spread
     // so that no instruction waits for the one before it and no transcendental directly follows
     // an MFMA (either would cost idle issue slots):
@@ -550,8 +589,9 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
       }
       if constexpr (j >= 1 && j <= 16) {
         constexpr int nbp = (j - 1) / 8;
-        sum[nbp] += ea + eb;
-        asm volatile("" : "+v"(sum[nbp]));
+        sum[nbp] += ea;
+        sum_b[nbp] += eb;
+        asm volatile("" : "+v"(sum[nbp]), "+v"(sum_b[nbp]));
         PL_SB();
       }
       if constexpr (j < 16) {
@@ -581,6 +621,11 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
         constexpr int nb = decltype(nb_tag)::value;
         // (the first MFMA of a group of PL_WG quanta waits for the group's fragments)
         constexpr bool wait_here = nb == 0 && j % PL_WG == 0;
+        // the period's five transfers ride behind the MFMAs of quanta 16 .. 18; in the steady
+        // state (no guards) each is fused with its MFMA
+        constexpr int d = 2 * (j - 16) + nb;
+        constexpr bool has_dma = d >= 0 && d < 5;
+        constexpr bool fused_dma = STEADY && has_dma;
         if constexpr (j == 0) {
           if constexpr (wait_here) pl_mfma_s_first_w(s_out[nb], fr[cur], qf[nb][j]);
           else pl_mfma_s_first(s_out[nb], fr[cur], qf[nb][j]);
@@ -589,8 +634,23 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
           else pl_mfma_s(s_out[nb], fr[cur], qf[nb][j]);
         } else {
           constexpr int kk = (j - 12) / 4, db = (j - 12) % 4;
-          if constexpr (wait_here) pl_mfma_o_w(o[db][nb], fr[cur], p_in[nb][kk]);
-          else pl_mfma_o(o[db][nb], fr[cur], p_in[nb][kk]);
+          if constexpr (fused_dma) {
+            // transfer d of the group: K fragments w, w + 4, w + 8 of block kg, then V fragments
+            // w, w + 4 of block kg - 3
+            if constexpr (d < 3)
+              pl_mfma_o_dma<wait_here>(o[db][nb], fr[cur], p_in[nb][kk], lane_off[d],
+                                       kbase + (size_t)kg * PL_K_BYTES,
+                                       lds_base + (kg & (PL_NK - 1)) * PL_K_BYTES + d * 4096);
+            else
+              pl_mfma_o_dma<wait_here>(o[db][nb], fr[cur], p_in[nb][kk], lane_off[d - 3],
+                                       vbase + (size_t)(kg - 3) * PL_V_BYTES,
+                                       lds_base + PL_V_BASE + ((kg - 3) & (PL_NV - 1)) * PL_V_BYTES +
+                                           (d - 3) * 4096);
+          } else if constexpr (wait_here) {
+            pl_mfma_o_w(o[db][nb], fr[cur], p_in[nb][kk]);
+          } else {
+            pl_mfma_o(o[db][nb], fr[cur], p_in[nb][kk]);
+          }
         }
         PL_SB();
         if constexpr (nb == 0) {
@@ -603,8 +663,7 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
         } else {
           part2(j_tag);
         }
-        constexpr int d = 2 * (j - 16) + nb;   // transfer 0..4 of the group
-        if constexpr (d >= 0 && d < 5) dma(std::integral_constant<int, (d >= 0 && d < 5) ? d : 0>{});
+        if constexpr (has_dma && !fused_dma) dma(std::integral_constant<int, has_dma ? d : 0>{});
         PL_SB();
       });
     });
@@ -618,8 +677,8 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
 #endif
       pl_mfma_drain();
     if (STEADY || t < nfull) {
-      l[0] += sum[0];
-      l[1] += sum[1];
+      l[0] += sum[0] + sum_b[0];
+      l[1] += sum[1] + sum_b[1];
     }
   };
 
@@ -955,9 +1014,9 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_token_split_kernel(PrefixA
     const __bf16* ks = kbase + ptb * K_BLK_ELEMS;
     const __bf16* vs = vbase + ptb * V_BLK_ELEMS;
 #pragma unroll
-    for (int f = 0; f < 12; f++) dma16(ks + f * 512, dst + f * 1024);
+    for (int f = 0; f < 12; f++) dma16_stream(ks + f * 512, dst + f * 1024);
 #pragma unroll
-    for (int f = 0; f < 8; f++) dma16(vs + f * 512, dst + K_BLK_ELEMS * 2 + f * 1024);
+    for (int f = 0; f < 8; f++) dma16_stream(vs + f * 512, dst + K_BLK_ELEMS * 2 + f * 1024);
   };
   const int first = tb0 + wave;
   const int nmine = first < tb1 ? (tb1 - first + 3) / 4 : 0;
