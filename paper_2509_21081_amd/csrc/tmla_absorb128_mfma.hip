@@ -151,13 +151,22 @@ __global__ void __launch_bounds__(256, 1) absorb128_kernel(Absorb128Args args) {
     if constexpr (K < 8) {
       const int r = wave + 4 * K;
       const int rr = min(r, s.last);
-      dma16_scalar_base(lane16 ^ (((wave << 2) | (K & 3)) << 4), s.lat + (size_t)rr * s.lat_stride,
-                        dst, r * 1024);
+      if (s.stream)
+        dma16_scalar_base<true>(lane16 ^ (((wave << 2) | (K & 3)) << 4),
+                                s.lat + (size_t)rr * s.lat_stride, dst, r * 1024);
+      else
+        dma16_scalar_base<false>(lane16 ^ (((wave << 2) | (K & 3)) << 4),
+                                 s.lat + (size_t)rr * s.lat_stride, dst, r * 1024);
     } else {
       const int rope_row = 8 * wave + (lane >> 3);
       const int rope_ch = ((lane & 7) ^ ((rope_row >> 1) & 7)) << 4;
       const int rr = min(rope_row, s.last);
-      dma16_scalar_base(rr * s.rope_stride + rope_ch, s.rope, dst, A128_MAIN_BYTES + wave * 1024);
+      if (s.stream)
+        dma16_scalar_base<true>(rr * s.rope_stride + rope_ch, s.rope, dst,
+                                A128_MAIN_BYTES + wave * 1024);
+      else
+        dma16_scalar_base<false>(rr * s.rope_stride + rope_ch, s.rope, dst,
+                                 A128_MAIN_BYTES + wave * 1024);
     }
   };
   auto issue_all = [&](const RowSrc& s, uint32_t dst) __attribute__((always_inline)) {
@@ -171,6 +180,7 @@ __global__ void __launch_bounds__(256, 1) absorb128_kernel(Absorb128Args args) {
   auto step_src = [&](int step, RowSrc& s0, RowSrc& s1) __attribute__((always_inline)) {
     const int tok0 = t0 + step * 64;
     s0.last = t1 - 1 - tok0;              // >= 0 for every step of the chunk
+    s0.stream = !is_prefix;               // the shared latent prefix is read by every request
     if (is_prefix) {
       s0.lat = (const char*)a.pc + (size_t)tok0 * (D_L * 2);
       s0.rope = (const char*)a.pr + (size_t)tok0 * (D_R * 2);

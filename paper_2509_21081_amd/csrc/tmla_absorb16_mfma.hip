@@ -143,7 +143,10 @@ __global__ void __launch_bounds__(256, 1) absorb16_kernel(Absorb16Args a) {
     for (int r = 0; r < 32; r++) {
       const int rr = min(r, last);
       const int loff = ((r >> 3) & 1) ? lane_off1 : lane_off0;
-      dma16_stream(base + (size_t)rr * row_bytes + loff, slot + r * A16_ROW_BYTES);
+      // (the shared latent prefix is read by every request: default policy; a request's own
+      // rows are streamed)
+      if constexpr (PREFIX) dma16(base + (size_t)rr * row_bytes + loff, slot + r * A16_ROW_BYTES);
+      else dma16_stream(base + (size_t)rr * row_bytes + loff, slot + r * A16_ROW_BYTES);
     }
 #pragma unroll
     for (int j = 0; j < 4; j++) {
@@ -153,7 +156,8 @@ __global__ void __launch_bounds__(256, 1) absorb16_kernel(Absorb16Args a) {
         src = (const char*)a.pr + (size_t)(tok0 + rr) * (D_R * 2) + (rope_ch ^ ((j & 1) << 6));
       else
         src = base + (size_t)rr * row_bytes + D_L * 2 + (rope_ch ^ ((j & 1) << 6));
-      dma16_stream(src, slot + A16_MAIN_BYTES + j * 1024);
+      if constexpr (PREFIX) dma16(src, slot + A16_MAIN_BYTES + j * 1024);
+      else dma16_stream(src, slot + A16_MAIN_BYTES + j * 1024);
     }
   };
   auto issue = [&](int tile) __attribute__((always_inline)) {

@@ -116,6 +116,7 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
   auto step_src = [&](int step, RowSrc& s0, RowSrc& s1) __attribute__((always_inline)) {
     const int tok0 = t0 + step * 64;
     s0.last = t1 - 1 - tok0;              // >= 0 for every step of the chunk
+    s0.stream = !is_prefix;               // the shared latent prefix is read by every request
     if (is_prefix) {
       s0.lat = (const char*)a.pc + (size_t)tok0 * (D_L * 2);
       s0.rope = (const char*)a.pr + (size_t)tok0 * (D_R * 2);
@@ -154,6 +155,7 @@ __global__ void __launch_bounds__(256, 1) absorb64_kernel(Absorb64Args args) {
     for (int j = 0; j < 2; j++) {
       const int blk_row0 = (qg * 2 + j) * 32;
       RowSrc qs;
+      qs.stream = false;
       qs.last = min(31, a.R - 1 - blk_row0);
       int64_t first = req_row0 + blk_row0;
       if (qs.last < 0) {   // block entirely past the request's rows: any valid row will do

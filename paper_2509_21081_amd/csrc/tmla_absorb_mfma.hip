@@ -77,6 +77,7 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
     RowSrc s;
     const int tok0 = t0 + tile * 32;
     s.last = t1 - 1 - tok0;              // last valid row of this tile (>= 0)
+    s.stream = !is_prefix;               // the shared latent prefix is read by every request
     if (is_prefix) {
       s.lat = (const char*)a.pc + (size_t)tok0 * (D_L * 2);
       s.rope = (const char*)a.pr + (size_t)tok0 * (D_R * 2);
@@ -114,6 +115,7 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
     for (int j = 0; j < NQB; j++) {
       const int blk_row0 = (qg * NQB + j) * 32;
       RowSrc qs;
+      qs.stream = false;
       qs.last = min(31, a.R - 1 - blk_row0);
       int64_t first = req_row0 + blk_row0;
       if (qs.last < 0) {   // block entirely past the request's rows: any valid row will do

@@ -85,6 +85,7 @@ struct RowSrc {
   const char* lat;
   const char* rope;
   int lat_stride, rope_stride, last;
+  bool stream;   // rows nobody else reads (a request's own suffix): non-temporal transfers
 };
 
 // Per-lane constants of the tile transfers (see the tile layout above).
@@ -110,10 +111,12 @@ __device__ __attribute__((always_inline)) inline void issue_part(const RowSrc& s
   if constexpr (K < 8) {
     const int r = d.wave + 4 * K;          // (r >> 2) & 3 == K & 3
     const int rr = min(r, s.last);
-    dma16_stream(s.lat + (size_t)rr * s.lat_stride + d.off[K & 3], dst + r * AB_ROW_BYTES);
+    if (s.stream) dma16_stream(s.lat + (size_t)rr * s.lat_stride + d.off[K & 3], dst + r * AB_ROW_BYTES);
+    else dma16(s.lat + (size_t)rr * s.lat_stride + d.off[K & 3], dst + r * AB_ROW_BYTES);
   } else {
     const int rr = min(d.rope_row, s.last);
-    dma16_stream(s.rope + (size_t)rr * s.rope_stride + d.rope_ch, dst + AB_MAIN_BYTES + d.wave * 1024);
+    if (s.stream) dma16_stream(s.rope + (size_t)rr * s.rope_stride + d.rope_ch, dst + AB_MAIN_BYTES + d.wave * 1024);
+    else dma16(s.rope + (size_t)rr * s.rope_stride + d.rope_ch, dst + AB_MAIN_BYTES + d.wave * 1024);
   }
 }
 __device__ __attribute__((always_inline)) inline void issue_all(const RowSrc& s, char* dst,

@@ -103,9 +103,12 @@ __device__ inline void raw_barrier() {
 __device__ inline void dma16(const void* src, void* dst) {
   __builtin_amdgcn_global_load_lds((glb_void_ptr)src, (lds_void_ptr)(lds_char_ptr)dst, 16, 0, 0);
 }
-// The same for data that is read once and never again (cache tiles of the attention kernels):
-// the non-temporal hint keeps the stream from displacing what the caches hold.  Measured on
-// MI355X: the HBM-bound kernels stream 11-13 % faster with it (5.8 instead of 5.1 TB/s).
+// The same for data that one workgroup reads once (a request's own cache rows, the expanded
+// prefix of a head): the non-temporal hint keeps the stream from displacing what the caches
+// hold.  Measured on MI355X: the HBM-bound kernels stream 11-13 % faster with it (5.8 instead of
+// 5.1 TB/s).  Data that every request reads again -- the latent prefix in absorb_only mode,
+// the absorbed queries -- keeps the default policy: streamed, the absorb_only pass over a
+// 16384-token prefix shared by 512 requests was 30 % slower.
 #ifndef TMLA_STREAM_AUX
 #define TMLA_STREAM_AUX 2   // aux bit 1 = nt
 #endif
@@ -121,6 +124,7 @@ __device__ inline void dma16_stream(const void* src, void* dst) {
 // 32-bit per-lane offset: no 64-bit vector additions per transfer.  `lds` + `lds2` = wave-uniform
 // LDS byte address (two terms so that the sum lands in M0 directly).  The statement sets M0 behind the compiler's back, which is safe only in kernels that
 // issue every global-to-LDS transfer through it and use nothing else that reads M0.
+template <bool STREAM = true>
 __device__ inline void dma16_scalar_base(uint32_t lane_off, const void* base, uint32_t lds,
                                          uint32_t lds2 = 0) {
   // wave-uniform by contract; made explicit so that both live in scalar registers
@@ -130,8 +134,12 @@ __device__ inline void dma16_scalar_base(uint32_t lane_off, const void* base, ui
   base = (const void*)(((uint64_t)hi << 32) | lo);
   lds = __builtin_amdgcn_readfirstlane(lds);
   lds2 = __builtin_amdgcn_readfirstlane(lds2);
-  asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" TMLA_STREAM_POLICY
-               ::"v"(lane_off), "s"(base), "s"(lds), "s"(lds2) : "memory", "scc");
+  if constexpr (STREAM)
+    asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" TMLA_STREAM_POLICY
+                 ::"v"(lane_off), "s"(base), "s"(lds), "s"(lds2) : "memory", "scc");
+  else
+    asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 ::"v"(lane_off), "s"(base), "s"(lds), "s"(lds2) : "memory", "scc");
 }
 
 // Scalar (SMEM) load of one int from a wave-uniform address.  A vector load here would have to be
