@@ -117,18 +117,19 @@ def cold_time(fn, iters, torch, dev):
     return sum(a.elapsed_time(b) for a, b in pairs) / iters
 
 
-def stage_times_in_step(step_mixed, T, torch, samples, L_s):
-    """Device time of each kernel stage INSIDE a running sequence of steps.  A sample is two
-    untimed full steps (they keep the stream busy while the host queues what follows, and leave
-    the caches as a step finds them in steady state) and then the four stages of one more step,
-    launched one by one through the library's single-stage switch, in the library's own order,
-    each between its own pair of HIP events on the launch stream."""
+def stage_times_in_step(step_mixed, T, torch, samples, L_s, lead_in=2):
+    """Device time of each kernel stage INSIDE a running sequence of steps.  A sample is a few
+    untimed full steps (`lead_in`: they keep the stream busy while the host queues what follows
+    -- about a millisecond's worth, so that no stage waits for the host -- and leave the caches
+    as a step finds them in steady state) and then the four stages of one more step, launched
+    one by one through the library's single-stage switch, in the library's own order, each
+    between its own pair of HIP events on the launch stream."""
     stream = torch.cuda.current_stream()
     stages = [(n, bit) for n, bit in STAGES if not (n == "prefix_attention" and L_s == 0)]
     acc = {n: 0.0 for n, _ in stages}
     for _ in range(samples):
-        step_mixed()
-        step_mixed()
+        for _ in range(lead_in):
+            step_mixed()
         evs = []
         try:
             for name, bit in stages:
@@ -280,7 +281,8 @@ def measure(case, steps, warmup, args, torch, T, C, dev):
     stage_ms = {}
     if not args.no_stages and case.spec.dtype == "bf16":
         stage_ms = stage_times_in_step(lambda: case.step("mixed"), T, torch,
-                                       max(5, min(20, steps // 2)), case.spec.prefix_len)
+                                       max(5, min(20, steps // 2)), case.spec.prefix_len,
+                                       lead_in=max(2, min(12, int(1.0 / ms["mixed"]) + 1)))
     per_kernel, roofline = kernel_rooflines(case, stage_ms, C)
     B, S = case.spec.batch, case.spec.q_len
     flops = 2 * C.table1_macs(case.shape, "mixed") + 2 * C.projection_macs(case.shape)
@@ -458,7 +460,8 @@ def bench_sweep(args, torch, T, C, W, dev):
                 for m in rounds:
                     rounds[m].append(event_time(lambda: case.step(m), steps, 2, torch))
             ms = {m: sorted(v)[len(v) // 2] for m, v in rounds.items()}
-            st = stage_times_in_step(lambda: case.step("mixed"), T, torch, 5, Ls)
+            st = stage_times_in_step(lambda: case.step("mixed"), T, torch, 5, Ls,
+                                     lead_in=max(2, min(12, int(1.0 / ms["mixed"]) + 1)))
             row = {"heads": H, "batch": B, "prefix_len": Ls, "ms_mixed": ms["mixed"], "ms_absorb_only": ms["absorb_only"],
                    "ms_auto": ms["auto"], "speedup_vs_absorb_only": ms["absorb_only"] / ms["mixed"],
                    "auto_vs_best": ms["auto"] / min(ms["mixed"], ms["absorb_only"]),
