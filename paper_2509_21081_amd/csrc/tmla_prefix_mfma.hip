@@ -358,6 +358,8 @@ constexpr int PL_LDS_BYTES = PL_V_BASE + PL_NV * PL_V_BYTES;      // 163840 = al
 static_assert((PL_NK & (PL_NK - 1)) == 0 && (PL_NV & (PL_NV - 1)) == 0, "slot = block & (n - 1)");
 constexpr int PL_D = 6;                                           // fragment reads in flight
 constexpr int PL_QUERIES = 256;
+constexpr int PL_OUT_ROW = 132;   // floats per row of the epilogue's LDS tile: 128 + 4 of padding
+static_assert(4 * 64 * PL_OUT_ROW * 4 <= PL_LDS_BYTES, "epilogue tiles fit the idle rings");
 #define PL_SB() __builtin_amdgcn_sched_barrier(0)
 
 // The MFMAs of the pipelined loop are written in assembly to fix where their operands live:
@@ -458,13 +460,8 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
                      "+a"(qf[nb][ks + 3])::"memory");
 
   // transfers: fragment f of a block is moved by wavefront f % 4 (K: 12 fragments, V: 8)
-#ifdef PL_PROBE_ALIAS   // timing probe only (wrong results): every head reads the cache of head h % PL_PROBE_ALIAS
-  const int hk = h % PL_PROBE_ALIAS;
-#else
-  const int hk = h;
-#endif
-  const char* kbase = (const char*)(a.pk + ((size_t)hk * a.ntb + tb0) * K_BLK_ELEMS);
-  const char* vbase = (const char*)(a.pv + ((size_t)hk * a.ntb + tb0) * V_BLK_ELEMS);
+  const char* kbase = (const char*)(a.pk + ((size_t)h * a.ntb + tb0) * K_BLK_ELEMS);
+  const char* vbase = (const char*)(a.pv + ((size_t)h * a.ntb + tb0) * V_BLK_ELEMS);
   const uint32_t lds_base = lds_addr(smem) + wave * 1024;
   uint32_t lane_off[3];   // fragment w, w + 4, w + 8 of a block
 #pragma unroll
@@ -537,15 +534,6 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
     bf16x8 (&p_in)[2][2] = pb[PAR ^ 1];
 
     sync(t, steady_tag);
-#ifdef PL_PROBE_NOMATH   // timing probe only (wrong results): the stream without the arithmetic
-    if constexpr (STEADY) {
-      const int kgp = t + PL_AHEAD;
-      dma_k(kgp, 0, NOGUARD{}); dma_k(kgp, 1, NOGUARD{}); dma_k(kgp, 2, NOGUARD{});
-      dma_v(kgp - 3, 0, NOGUARD{}); dma_v(kgp - 3, 1, NOGUARD{});
-      if (PL_PROBE_NOMATH > 0) __builtin_amdgcn_s_sleep(PL_PROBE_NOMATH);
-      return;
-    }
-#endif
     const uint32_t ka1 = lane_addr + ((t + 1) & (PL_NK - 1)) * PL_K_BYTES;   // K(t+1)
     const uint32_t ka2 = lane_addr + ((t + 2) & (PL_NK - 1)) * PL_K_BYTES;   // K(t+2)
     const uint32_t va =                                                // V(t-1), or K(0)
@@ -858,24 +846,51 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
     exact_maxima();
   }
 
+  // Epilogue.  As MFMA output a lane holds 16-byte pieces of its query's partial row, 32 bytes
+  // apart from its neighbour's: stored that way every instruction scatters 64 pieces of 32 B
+  // over 32 rows, and the burst of all workgroups at once took 10 us of a launch.  The rings are
+  // idle now (every transfer has landed, everyone is past the last barrier), so each wavefront
+  // turns its 64 x 128 tile around in a private LDS region and 32 lanes store one row's 512
+  // contiguous bytes.  A row that saw nothing (l = 0) is left unwritten: its LSE is -inf.
+  {
+    // (after a second walk nobody has met at a barrier yet: the other wavefronts may still be
+    // reading the rings, and their last transfers may still be landing)
+    vm_wait<0>();
+    lgkm_wait<0>();
+    raw_barrier();
+    float* tile = (float*)smem + wave * (64 * PL_OUT_ROW);
+    bool row_ok[2];
 #pragma unroll
-  for (int nb = 0; nb < 2; nb++) {
-    const int qi = q0 + nb * 32 + n;
-    if (qi >= a.M) continue;
-    const size_t row = (size_t)sp * a.rows + (size_t)qi * a.H + h;
-    if (lt[nb] > 0.f) {
-      const float inv = 1.f / lt[nb];
+    for (int nb = 0; nb < 2; nb++) {
+      const int qi = q0 + nb * 32 + n;
+      row_ok[nb] = qi < a.M && lt[nb] > 0.f;
+      const float inv = row_ok[nb] ? 1.f / lt[nb] : 0.f;
 #pragma unroll
       for (int db = 0; db < 4; db++)
 #pragma unroll
         for (int v4 = 0; v4 < 4; v4++) {
-          float4 w = make_float4(o[db][nb][4 * v4] * inv, o[db][nb][4 * v4 + 1] * inv,
-                                 o[db][nb][4 * v4 + 2] * inv, o[db][nb][4 * v4 + 3] * inv);
-          *(float4*)(a.o + row * D_V + 32 * db + 8 * v4 + 4 * g) = w;
+          const float4 w = make_float4(o[db][nb][4 * v4] * inv, o[db][nb][4 * v4 + 1] * inv,
+                                       o[db][nb][4 * v4 + 2] * inv, o[db][nb][4 * v4 + 3] * inv);
+          *(float4*)(tile + (nb * 32 + n) * PL_OUT_ROW + 32 * db + 8 * v4 + 4 * g) = w;
         }
-      if (g == 0) a.lse[row] = (m[nb] + fast_log2(lt[nb])) * LN2;
-    } else if (g == 0) {
-      a.lse[row] = -INFINITY;
+      if (qi < a.M && g == 0) {
+        const size_t row = (size_t)sp * a.rows + (size_t)qi * a.H + h;
+        a.lse[row] = row_ok[nb] ? (m[nb] + fast_log2(lt[nb])) * LN2 : -INFINITY;
+      }
+    }
+    // which of this wavefront's 64 rows are written: one bit per row, from the lanes that own them
+    const uint64_t ok0 = __builtin_amdgcn_ballot_w64(row_ok[0] && g == 0);
+    const uint64_t ok1 = __builtin_amdgcn_ballot_w64(row_ok[1] && g == 0);
+    const uint64_t ok = (ok0 & 0xffffffffull) | (ok1 << 32);
+    // (each wavefront reads back only what it wrote itself: no barrier)
+#pragma unroll 4
+    for (int i = 0; i < 32; i++) {
+      const int r = 2 * i + g;                       // row of the tile: query q0 + r
+      const float4 w = *(const float4*)(tile + r * PL_OUT_ROW + 4 * n);
+      if ((ok >> r) & 1) {
+        const size_t row = (size_t)sp * a.rows + (size_t)(q0 + r) * a.H + h;
+        *(float4*)(a.o + row * D_V + 4 * n) = w;
+      }
     }
   }
 }
