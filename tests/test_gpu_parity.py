@@ -48,6 +48,18 @@ SMALL_CASES = {
     # suffix lengths straddling the 32/64-token tile and step boundaries, causal over 3 queries
     "h32_step_edges": dict(batch=9, heads=32, q_len=3, prefix_len=64, suffix_min=61,
                            suffix_max=69, seed=34),
+    # the largest supported query length: 8 positions x 16 heads = 128 rows per request (the
+    # causal edge runs through one workgroup's rows), and x 32 heads = 256 rows
+    "qlen8_h16": dict(batch=3, heads=16, q_len=8, prefix_len=70, suffix_min=3, suffix_max=200,
+                      seed=35),
+    "qlen8_h32": dict(batch=2, heads=32, q_len=8, prefix_len=40, suffix_min=8, suffix_max=150,
+                      seed=36),
+    # more requests than the device-side ranking of suffix lengths handles (4096): batch order
+    "batch_5000": dict(batch=5000, heads=16, q_len=1, prefix_len=64, suffix_min=0, suffix_max=20,
+                       seed=37),
+    # one long suffix: the per-request chunk bound is reached and chunks grow instead
+    "long_suffix": dict(batch=2, heads=16, q_len=1, prefix_len=40, suffix_min=9000,
+                        suffix_max=9500, seed=38),
 }
 
 _cache = {}
