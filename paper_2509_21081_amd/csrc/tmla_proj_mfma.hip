@@ -426,6 +426,91 @@ __global__ void __launch_bounds__(256) finalize_few_kernel(FinalizeArgs a) {
   else finalize_tail(a, row, wave, g, l_a, oa);
 }
 
+// One latent partial (the suffix is in one chunk -- every large batch) and many queries per head:
+// a workgroup takes QB consecutive blocks of 32 queries of its head with W_UV[h] resident in
+// registers, instead of fetching the 128 KiB of weights once per 32 queries.  A compute unit
+// takes in data at a limited rate, and with one block per workgroup two thirds of what it takes
+// in are weights.  Nothing is double-buffered: a register set is refilled for the next block as
+// soon as the current block has used it (the latent partial behind the MFMAs, the naive partials
+// behind the merge), so each round trip runs alongside the other half of the work.
+template <int NN, int QB>
+__global__ void __launch_bounds__(256) finalize_blocks_kernel(FinalizeArgs a) {
+  __shared__ float red[4][4][16][64];        // [wavefront][value block][acc register][lane]
+  const int nqb = (a.M + 31) / 32, ngrp = (nqb + QB - 1) / QB;
+  const int id = blockIdx.x, sl = id >> 3;
+  const int qg = sl % ngrp, h = (sl / ngrp) * 8 + (id & 7);   // groups of a head: same XCD
+  if (h >= a.H) return;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, g = lane >> 5;
+
+  const __bf16* wp = a.w_uv + ((size_t)h * D_V + n) * D_L + 8 * g + 128 * wave;
+  bf16x8 wf[8][4];
+#pragma unroll
+  for (int ks = 0; ks < 8; ks++)
+#pragma unroll
+    for (int mb = 0; mb < 4; mb++)
+      wf[ks][mb] = *(const bf16x8*)(wp + (size_t)(32 * mb) * D_L + 16 * ks);
+
+  const int qb0 = qg * QB;
+  auto row_of = [&](int qb) { const int qi = qb * 32 + n; return qi < a.M ? (size_t)qi * a.H + h : (size_t)h; };
+  float ll;
+  bf16x8 x[8];
+  NaivePrefetch<NN> pre;
+  auto load_latent = [&](int qb) __attribute__((always_inline)) {
+    const size_t row = row_of(qb);
+    ll = a.lat_lse[row];
+    const __bf16* lp = a.lat_o + row * D_L + 8 * g + 128 * wave;
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) x[ks] = *(const bf16x8*)(lp + 16 * ks);
+  };
+  load_latent(qb0);
+  prefetch_naive(a, row_of(qb0), wave, g, pre);
+#pragma unroll
+  for (int ks = 0; ks < 8; ks++)
+    asm volatile("" : "+v"(wf[ks][0]), "+v"(wf[ks][1]), "+v"(wf[ks][2]), "+v"(wf[ks][3]), "+v"(x[ks]));
+
+  for (int it = 0; it < QB; it++) {
+    const int qb = qb0 + it;
+    if (qb >= nqb) break;                      // workgroup-uniform
+    const int qi = qb * 32 + n;
+    const bool valid = qi < a.M;
+    const size_t row = row_of(qb);
+    // a single partial is already the merged latent output (weight 1, or 0 if it saw nothing)
+    const bool any = ll > -INFINITY && valid;
+    const float l_a = any ? ll : -INFINITY;
+    f32x16 acc[4];
+#pragma unroll
+    for (int mb = 0; mb < 4; mb++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[mb][v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) {
+      const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+      const bf16x8 bfrag = any ? x[ks] : zero;
+#pragma unroll
+      for (int mb = 0; mb < 4; mb++) acc[mb] = mfma32(wf[ks][mb], bfrag, acc[mb]);
+    }
+    // the latent registers are free: the next block's partial is requested now and arrives
+    // while this block is reduced, merged and stored
+    const bool more = it + 1 < QB && qb + 1 < nqb;
+    if (more) load_latent(qb + 1);
+#pragma unroll
+    for (int mb = 0; mb < 4; mb++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) red[wave][mb][v][lane] = acc[mb][v];
+    __syncthreads();
+    float oa[16];
+#pragma unroll
+    for (int v = 0; v < 16; v++)
+      oa[v] = red[0][wave][v][lane] + red[1][wave][v][lane] + red[2][wave][v][lane] +
+              red[3][wave][v][lane];
+    if (valid) finalize_tail_prefetched(a, row, wave, g, l_a, oa, pre);
+    // likewise the naive partials: requested behind their last use, needed after the next
+    // block's MFMAs
+    if (more) prefetch_naive(a, row_of(qb + 1), wave, g, pre);
+    __syncthreads();                           // the reduction buffer is reused
+  }
+}
+
 template <int NL>
 static void launch_finalize_few(const FinalizeArgs& a, dim3 grid, hipStream_t stream) {
   // The prefetch costs 34 registers, which halves the wavefronts per SIMD: it pays only where a
@@ -450,6 +535,27 @@ int mfma_finalize(const Plan& p, const DecodeArgs& d) {
   a.out = (__bf16*)d.out;
   a.lse_out = d.lse_out;
   a.M = p.B * p.Sq; a.H = p.H; a.n_naive = p.n_naive; a.n_lat = p.n_lat; a.rows = p.rows;
+  // one latent partial, one or two naive partials, and enough query blocks per head that groups
+  // of them still cover the chip: the kernel that keeps a head's weights for several blocks
+  if (p.n_lat == 1 && (p.n_naive == 1 || p.n_naive == 2)) {
+    const int nqb = (a.M + 31) / 32;
+    const int heads8 = (p.H + 7) / 8 * 8;
+    int qbk = 0;
+    if (heads8 * ((nqb + 3) / 4) >= NUM_CU) qbk = 4;
+    else if (heads8 * ((nqb + 1) / 2) >= NUM_CU) qbk = 2;
+    if (qbk) {
+      dim3 gridb(heads8 * ((nqb + qbk - 1) / qbk));
+      if (qbk == 4 && p.n_naive == 1)
+        hipLaunchKernelGGL((finalize_blocks_kernel<1, 4>), gridb, dim3(256), 0, d.stream, a);
+      else if (qbk == 4)
+        hipLaunchKernelGGL((finalize_blocks_kernel<2, 4>), gridb, dim3(256), 0, d.stream, a);
+      else if (p.n_naive == 1)
+        hipLaunchKernelGGL((finalize_blocks_kernel<1, 2>), gridb, dim3(256), 0, d.stream, a);
+      else
+        hipLaunchKernelGGL((finalize_blocks_kernel<2, 2>), gridb, dim3(256), 0, d.stream, a);
+      return TMLA_OK;
+    }
+  }
   dim3 grid(8 * ((a.M + 31) / 32) * ((p.H + 7) / 8));
   switch (p.n_lat) {
     case 1: launch_finalize_few<1>(a, grid, d.stream); break;
