@@ -317,6 +317,25 @@ def test_combine_lse_matches_definition(n, rows, width, out_dtype, gpu_device):
     np.testing.assert_allclose(got_l[fin], ref_l[fin], atol=1e-5, rtol=1e-6)
 
 
+@pytest.mark.parametrize("mode", ["mixed", "absorb_only"])
+def test_large_batch_projection_kernels(mode, gpu_device):
+    """More than 1024 queries per head at 64 heads: the query absorption stages a weight slice once
+    for four blocks of 128 queries, and the up-projection keeps a head's weights for four blocks
+    of 32 -- both with a ragged last group (1100 = 8 x 128 + 76 = 34 x 32 + 12 queries).  Every
+    row against the tensor-form absorb checker, a sample against the definition."""
+    spec = W.small_spec(name="large_batch_h64", dtype="bf16", batch=1100, heads=64, q_len=1,
+                        prefix_len=64, suffix_min=0, suffix_max=24, seed=55)
+    wl = W.make_workload(spec)
+    a = wl.as_float64()
+    ref2, ref2_lse = Hh.oracle_absorb_all_heads_parallel(O, a)
+    pairs = [(b, h) for b in (0, 1, 511, 1023, 1024, 1099) for h in (0, 31, 63)]
+    ref, ref_lse = O.mla_decode_definition(**a, pairs=pairs)
+    print(f"large batch projections mode={mode}", flush=True)
+    got, got_lse = Hh.run_library(wl, mode, gpu_device)
+    Hh.assert_parity(got, got_lse, ref2, ref2_lse, "bf16", f"large_batch/{mode}/absorb-form")
+    Hh.assert_parity(got, got_lse, ref, ref_lse, "bf16", f"large_batch/{mode}/definition")
+
+
 @pytest.mark.parametrize("mode", MODES)
 def test_bitwise_repeatable(mode, gpu_device):
     wl, _ = _workload_and_ref("ragged_h16", "bf16")
