@@ -24,7 +24,9 @@
 
 namespace tmla {
 
-template <int NQB>
+// HAS_PREFIX: the launch has work items over the shared latent prefix (absorb_only mode); then
+// every transfer is an ordinary one (see the 64-row kernel), else the suffix rows are streamed.
+template <int NQB, bool HAS_PREFIX>
 __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
   constexpr int NLP = 4 / NQB;
   constexpr int MBW = 16 / NLP;  // 32-latent blocks owned by a wavefront
@@ -40,7 +42,7 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
 
   // ---- which tokens
   int t0, t1, vis_q;
-  const bool is_prefix = item < a.ap_chunks;
+  const bool is_prefix = HAS_PREFIX && item < a.ap_chunks;
   if (is_prefix) {
     t0 = item * a.ap_chunk;
     t1 = min(a.Ls, t0 + a.ap_chunk);
@@ -77,7 +79,7 @@ __global__ void __launch_bounds__(256, 1) absorb_attn_kernel(AbsorbArgs a) {
     RowSrc s;
     const int tok0 = t0 + tile * 32;
     s.last = t1 - 1 - tok0;              // last valid row of this tile (>= 0)
-    s.stream = !is_prefix;               // the shared latent prefix is read by every request
+    s.stream = !HAS_PREFIX;
     if (is_prefix) {
       s.lat = (const char*)a.pc + (size_t)tok0 * (D_L * 2);
       s.rope = (const char*)a.pr + (size_t)tok0 * (D_R * 2);
@@ -354,11 +356,12 @@ int mfma_absorb_attention(const Plan& p, const DecodeArgs& d) {
       ((debug_flags() & 0x2000) || (long long)p.n_lat * p.B * (a.R / 128) >= NUM_CU))
     return mfma_absorb128_attention(p, d, a);
   if (a.R > 32) return mfma_absorb64_attention(p, d, a);
-  static LdsOptIn lds;
-  if (lds.ensure((const void*)absorb_attn_kernel<1>, AB_LDS_BYTES) != hipSuccess) return TMLA_ERR_HIP;
+  static LdsOptIn lds[2];
+  auto kernel = a.ap_chunks > 0 ? absorb_attn_kernel<1, true> : absorb_attn_kernel<1, false>;
+  if (lds[a.ap_chunks > 0].ensure((const void*)kernel, AB_LDS_BYTES) != hipSuccess) return TMLA_ERR_HIP;
   dim3 grid(p.n_lat, 1, p.B);
   a.order = suffix_request_order(p, d, (long long)p.n_lat * p.B);
-  hipLaunchKernelGGL(absorb_attn_kernel<1>, grid, dim3(256), AB_LDS_BYTES, d.stream, a);
+  hipLaunchKernelGGL(kernel, grid, dim3(256), AB_LDS_BYTES, d.stream, a);
   return TMLA_OK;
 }
 
