@@ -7,6 +7,7 @@
 // Both are per-head GEMMs with the queries on the MFMA column axis (transposed products, see
 // tmla_mfma.hpp), so all per-query softmax weights are per-lane scalars.
 #include "tmla_common.hpp"
+#include "tmla_lds_asm.hpp"
 #include "tmla_mfma.hpp"
 
 namespace tmla {
@@ -450,88 +451,168 @@ __global__ void __launch_bounds__(256) finalize_few_kernel(FinalizeArgs a) {
 }
 
 // One latent partial (the suffix is in one chunk -- every large batch) and many queries per head:
-// a workgroup takes QB consecutive blocks of 32 queries of its head with W_UV[h] resident in
-// registers, instead of fetching the 128 KiB of weights once per 32 queries.  A compute unit
-// takes in data at a limited rate, and with one block per workgroup two thirds of what it takes
-// in are weights.  Nothing is double-buffered: a register set is refilled for the next block as
-// soon as the current block has used it (the latent partial behind the MFMAs, the naive partials
-// behind the merge), so each round trip runs alongside the other half of the work.
-template <int NN, int QB>
-__global__ void __launch_bounds__(256) finalize_blocks_kernel(FinalizeArgs a) {
-  __shared__ float red[4][4][16][64];        // [wavefront][value block][acc register][lane]
-  const int nqb = (a.M + 31) / 32, ngrp = (nqb + QB - 1) / QB;
+// a workgroup takes a run of consecutive blocks of 32 queries of its head with its share of
+// W_UV[h] resident in registers, and the partials of a block -- 32 latent rows of 1 KiB and the
+// 32 x 512 B of each naive partial -- stream through an LDS ring of whole blocks, one or two
+// blocks ahead of their use.  Wavefront w owns value columns [32 w, 32 w + 32) over the whole
+// contraction, so nothing is summed across wavefronts; the latent rows in LDS are shared by all
+// four.  A compute unit takes in data at a limited rate and every request here is a full
+// contiguous row (the per-lane fragment loads of the other kernels fetch 32 bytes per row and
+// instruction), which is what this kernel is about: it is bound by memory, not by its 32 MFMAs
+// per block and wavefront.
+//   LDS slot: latent row r at r * 1024, its 16-byte chunk c in place c ^ (r & 15) (the reads of
+//   a k-step take one chunk from each of 16 rows: the swizzle spreads them over the banks);
+//   behind it naive partial i, row r at r * 512, chunk c (of 32) in place c ^ (r & 15).
+// vmcnt bookkeeping: a block's transfers are the youngest memory operations but for the
+// transfers of the blocks behind it, so "at most TPW * (FS_NSLOT - 2) in flight" means it landed
+// (stores in between only make the wait stricter).
+constexpr int FS_X_BYTES = 32 * 1024;
+constexpr int FS_N_BYTES = 32 * 512;
+template <int NN>
+struct FsLayout {
+  static constexpr int NSLOT = NN == 1 ? 3 : 2;
+  static constexpr int SLOT = FS_X_BYTES + NN * FS_N_BYTES;
+  static constexpr int BYTES = NSLOT * SLOT;     // 144 KiB (one naive partial), 128 KiB (two)
+  static constexpr int TPW = 8 + 4 * NN;         // transfers per wavefront and block
+};
+
+template <int NN>
+__global__ void __launch_bounds__(256, 1) finalize_stream_kernel(FinalizeArgs a, int qbk) {
+  using L = FsLayout<NN>;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int nqb = (a.M + 31) / 32, ngrp = (nqb + qbk - 1) / qbk;
   const int id = blockIdx.x, sl = id >> 3;
   const int qg = sl % ngrp, h = (sl / ngrp) * 8 + (id & 7);   // groups of a head: same XCD
   if (h >= a.H) return;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 31, g = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, n = lane & 31, g = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int qb0 = qg * qbk, nblk = min(qbk, nqb - qb0);
 
-  const __bf16* wp = a.w_uv + ((size_t)h * D_V + n) * D_L + 8 * g + 128 * wave;
-  bf16x8 wf[8][4];
-#pragma unroll
-  for (int ks = 0; ks < 8; ks++)
-#pragma unroll
-    for (int mb = 0; mb < 4; mb++)
-      wf[ks][mb] = *(const bf16x8*)(wp + (size_t)(32 * mb) * D_L + 16 * ks);
-
-  const int qb0 = qg * QB;
-  auto row_of = [&](int qb) { const int qi = qb * 32 + n; return qi < a.M ? (size_t)qi * a.H + h : (size_t)h; };
-  float ll;
-  bf16x8 x[8];
-  NaivePrefetch<NN> pre;
-  auto load_latent = [&](int qb) __attribute__((always_inline)) {
-    const size_t row = row_of(qb);
-    ll = a.lat_lse[row];
-    const __bf16* lp = a.lat_o + row * D_L + 8 * g + 128 * wave;
-#pragma unroll
-    for (int ks = 0; ks < 8; ks++) x[ks] = *(const bf16x8*)(lp + 16 * ks);
+  auto row_of = [&](int qb, int r) {
+    const int qi = qb * 32 + r;
+    return qi < a.M ? (size_t)qi * a.H + h : (size_t)h;
   };
-  load_latent(qb0);
-  prefetch_naive(a, row_of(qb0), wave, g, pre);
+  // the transfers of block qb into ring slot `slot` issued by this wavefront: latent rows
+  // wave, wave + 4, ...; pairs of naive rows 2 t, 2 t + 1 for t = wave, wave + 4, ...
+  auto issue_block = [&](int qb, int slot) __attribute__((always_inline)) {
+    char* dst = smem + slot * L::SLOT;
 #pragma unroll
-  for (int ks = 0; ks < 8; ks++)
-    asm volatile("" : "+v"(wf[ks][0]), "+v"(wf[ks][1]), "+v"(wf[ks][2]), "+v"(wf[ks][3]), "+v"(x[ks]));
-
-  for (int it = 0; it < QB; it++) {
-    const int qb = qb0 + it;
-    if (qb >= nqb) break;                      // workgroup-uniform
-    const int qi = qb * 32 + n;
-    const bool valid = qi < a.M;
-    const size_t row = row_of(qb);
-    // a single partial is already the merged latent output (weight 1, or 0 if it saw nothing)
-    const bool any = ll > -INFINITY && valid;
-    const float l_a = any ? ll : -INFINITY;
-    f32x16 acc[4];
-#pragma unroll
-    for (int mb = 0; mb < 4; mb++)
-#pragma unroll
-      for (int v = 0; v < 16; v++) acc[mb][v] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < 8; ks++) {
-      const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-      const bf16x8 bfrag = any ? x[ks] : zero;
-#pragma unroll
-      for (int mb = 0; mb < 4; mb++) acc[mb] = mfma32(wf[ks][mb], bfrag, acc[mb]);
+    for (int k = 0; k < 8; k++) {
+      const int r = wave + 4 * k;
+      const char* src = (const char*)(a.lat_o + row_of(qb, r) * D_L);
+      dma16(src + ((lane ^ (r & 15)) << 4), dst + r * 1024);
     }
-    // the latent registers are free: the next block's partial is requested now and arrives
-    // while this block is reduced, merged and stored
-    const bool more = it + 1 < QB && qb + 1 < nqb;
-    if (more) load_latent(qb + 1);
 #pragma unroll
-    for (int mb = 0; mb < 4; mb++)
+    for (int i = 0; i < NN; i++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) red[wave][mb][v][lane] = acc[mb][v];
-    __syncthreads();
+      for (int k = 0; k < 4; k++) {
+        const int t = wave + 4 * k, r = 2 * t + g;
+        const char* src = (const char*)(a.naive_o + ((size_t)i * a.rows + row_of(qb, r)) * D_V);
+        dma16(src + ((n ^ (r & 15)) << 4), dst + FS_X_BYTES + i * FS_N_BYTES + t * 1024);
+      }
+  };
+  struct Lse { float lat, naive[NN]; };
+  auto load_lse = [&](int qb, Lse& l) __attribute__((always_inline)) {
+    const size_t row = row_of(qb, n);
+    l.lat = a.lat_lse[row];
+#pragma unroll
+    for (int i = 0; i < NN; i++) l.naive[i] = a.naive_lse[(size_t)i * a.rows + row];
+  };
+
+  // W_UV[h][32 wave + n][16 ks + 8 g ..]: the A fragments of all 32 k-steps
+  bf16x8 wf[32];
+  {
+    const __bf16* wp = a.w_uv + ((size_t)h * D_V + 32 * wave + n) * D_L + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < 32; ks++) wf[ks] = *(const bf16x8*)(wp + 16 * ks);
+  }
+  Lse lse_cur, lse_next;
+  load_lse(qb0, lse_cur);
+  lse_next = lse_cur;
+#pragma unroll
+  for (int j = 0; j < L::NSLOT - 1; j++)
+    if (j < nblk) issue_block(qb0 + j, j);
+
+  const uint32_t smem_base = lds_addr(smem);
+  const uint32_t x_lane = n * 1024 + ((g ^ (n & 15)) << 4);
+  const uint32_t n_lane = FS_X_BYTES + n * 512;
+  int slot = 0;
+  for (int it = 0; it < nblk; it++) {
+    const int qb = qb0 + it;
+    // block `it` has landed when only the transfers of the blocks behind it are in flight
+    if (L::NSLOT == 3 && it + 1 < nblk) vm_wait<L::TPW>();
+    else vm_wait<0>();
+    raw_barrier();   // everybody's part of the block is there; everybody is done with block it - 1
+    if (it + 1 < nblk) load_lse(qb + 1, lse_next);
+    if (it + L::NSLOT - 1 < nblk) {
+      int fill = slot - 1;
+      if (fill < 0) fill += L::NSLOT;
+      issue_block(qb + L::NSLOT - 1, fill);
+    }
+    const uint32_t sb = smem_base + slot * L::SLOT;
+    const bool valid = qb * 32 + n < a.M;
+    // a single partial is already the merged latent output (weight 1, or 0 if it saw nothing:
+    // then its row was never written and is replaced by zeros)
+    const bool any = lse_cur.lat > -INFINITY && valid;
+    const float l_a = any ? lse_cur.lat : -INFINITY;
+
+    // ---- up-projection: fragments through a ring of eight registers, eight reads ahead
+    uint32_t xa[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) xa[j] = (sb + x_lane) ^ (j << 5);
+    bf16x8 fr[8];
+    static_for<8>([&](auto j_) {
+      constexpr int j = decltype(j_)::value;
+      fr[j] = lds_read_b128<0>(xa[j]);
+    });
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; v++) acc[v] = 0.f;
+    static_for<32>([&](auto ks_) {
+      constexpr int ks = decltype(ks_)::value;
+      constexpr int later = 31 - ks < 7 ? 31 - ks : 7;
+      lgkm_wait<later>(fr[ks % 8]);
+      const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+      const bf16x8 bfrag = any ? fr[ks % 8] : zero;
+      acc = mfma32(wf[ks], bfrag, acc);
+      if constexpr (ks + 8 < 32) fr[ks % 8] = lds_read_b128<256 * ((ks + 8) >> 3)>(xa[ks % 8]);
+    });
+
+    // ---- the naive partials of this lane's value columns, then merge, normalise, store
+    NaivePrefetch<NN> pre;
+#pragma unroll
+    for (int i = 0; i < NN; i++) {
+      pre.lse[i] = lse_cur.naive[i];
+#pragma unroll
+      for (int v4 = 0; v4 < 4; v4++) {
+        const int c = 8 * wave + 2 * v4 + g;
+        pre.o[i][v4] = lds_read_f32x4(sb + n_lane + i * FS_N_BYTES + ((c ^ (n & 15)) << 4));
+      }
+    }
     float oa[16];
 #pragma unroll
-    for (int v = 0; v < 16; v++)
-      oa[v] = red[0][wave][v][lane] + red[1][wave][v][lane] + red[2][wave][v][lane] +
-              red[3][wave][v][lane];
-    if (valid) finalize_tail_prefetched(a, row, wave, g, l_a, oa, pre);
-    // likewise the naive partials: requested behind their last use, needed after the next
-    // block's MFMAs
-    if (more) prefetch_naive(a, row_of(qb + 1), wave, g, pre);
-    __syncthreads();                           // the reduction buffer is reused
+    for (int v = 0; v < 16; v++) oa[v] = acc[v];
+#pragma unroll
+    for (int i = 0; i < NN; i++)
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(pre.o[i][0]), "+v"(pre.o[i][1]), "+v"(pre.o[i][2]), "+v"(pre.o[i][3])
+                   :: "memory");
+    if (valid) finalize_tail_prefetched(a, row_of(qb, n), wave, g, l_a, oa, pre);
+    lse_cur = lse_next;
+    slot = slot + 1 == L::NSLOT ? 0 : slot + 1;
   }
+}
+
+template <int NN>
+static int launch_finalize_stream(const FinalizeArgs& a, int heads8, int nqb, int qbk,
+                                  hipStream_t stream) {
+  static LdsOptIn lds;
+  if (lds.ensure((const void*)finalize_stream_kernel<NN>, FsLayout<NN>::BYTES) != hipSuccess)
+    return TMLA_ERR_HIP;
+  dim3 grid(heads8 * ((nqb + qbk - 1) / qbk));
+  hipLaunchKernelGGL(finalize_stream_kernel<NN>, grid, dim3(256), FsLayout<NN>::BYTES, stream, a,
+                     qbk);
+  return TMLA_OK;
 }
 
 template <int NL>
@@ -558,26 +639,16 @@ int mfma_finalize(const Plan& p, const DecodeArgs& d) {
   a.out = (__bf16*)d.out;
   a.lse_out = d.lse_out;
   a.M = p.B * p.Sq; a.H = p.H; a.n_naive = p.n_naive; a.n_lat = p.n_lat; a.rows = p.rows;
-  // one latent partial, one or two naive partials, and enough query blocks per head that groups
-  // of them still cover the chip: the kernel that keeps a head's weights for several blocks
+  // one latent partial, one or two naive partials, and at least two blocks of 32 queries per
+  // compute unit: runs of up to eight blocks per workgroup, so that the grid still covers the chip
   if (p.n_lat == 1 && (p.n_naive == 1 || p.n_naive == 2)) {
     const int nqb = (a.M + 31) / 32;
     const int heads8 = (p.H + 7) / 8 * 8;
-    int qbk = 0;
-    if (heads8 * ((nqb + 3) / 4) >= NUM_CU) qbk = 4;
-    else if (heads8 * ((nqb + 1) / 2) >= NUM_CU) qbk = 2;
-    if (qbk) {
-      dim3 gridb(heads8 * ((nqb + qbk - 1) / qbk));
-      if (qbk == 4 && p.n_naive == 1)
-        hipLaunchKernelGGL((finalize_blocks_kernel<1, 4>), gridb, dim3(256), 0, d.stream, a);
-      else if (qbk == 4)
-        hipLaunchKernelGGL((finalize_blocks_kernel<2, 4>), gridb, dim3(256), 0, d.stream, a);
-      else if (p.n_naive == 1)
-        hipLaunchKernelGGL((finalize_blocks_kernel<1, 2>), gridb, dim3(256), 0, d.stream, a);
-      else
-        hipLaunchKernelGGL((finalize_blocks_kernel<2, 2>), gridb, dim3(256), 0, d.stream, a);
-      return TMLA_OK;
-    }
+    const long long per_cu = (long long)heads8 * nqb / NUM_CU;
+    const int qbk = (int)(per_cu > 8 ? 8 : per_cu);
+    if (qbk >= 2)
+      return p.n_naive == 1 ? launch_finalize_stream<1>(a, heads8, nqb, qbk, d.stream)
+                            : launch_finalize_stream<2>(a, heads8, nqb, qbk, d.stream);
   }
   dim3 grid(8 * ((a.M + 31) / 32) * ((p.H + 7) / 8));
   switch (p.n_lat) {
