@@ -320,9 +320,10 @@ def test_combine_lse_matches_definition(n, rows, width, out_dtype, gpu_device):
 @pytest.mark.parametrize("mode", ["mixed", "absorb_only"])
 def test_large_batch_projection_kernels(mode, gpu_device):
     """More than 1024 queries per head at 64 heads: the query absorption stages a weight slice once
-    for four blocks of 128 queries, and the up-projection keeps a head's weights for four blocks
-    of 32 -- both with a ragged last group (1100 = 8 x 128 + 76 = 34 x 32 + 12 queries).  Every
-    row against the tensor-form absorb checker, a sample against the definition."""
+    for four blocks of 128 queries, and the up-projection streams runs of eight blocks of 32
+    through its LDS ring (three slots, one naive partial) -- both with a ragged last group
+    (1100 = 8 x 128 + 76 = 34 x 32 + 12 queries: runs of 8, 8, 8, 8 and 3 blocks).  Every row
+    against the tensor-form absorb checker, a sample against the definition."""
     spec = W.small_spec(name="large_batch_h64", dtype="bf16", batch=1100, heads=64, q_len=1,
                         prefix_len=64, suffix_min=0, suffix_max=24, seed=55)
     wl = W.make_workload(spec)
@@ -334,6 +335,24 @@ def test_large_batch_projection_kernels(mode, gpu_device):
     got, got_lse = Hh.run_library(wl, mode, gpu_device)
     Hh.assert_parity(got, got_lse, ref2, ref2_lse, "bf16", f"large_batch/{mode}/absorb-form")
     Hh.assert_parity(got, got_lse, ref, ref_lse, "bf16", f"large_batch/{mode}/definition")
+
+
+def test_streaming_upprojection_two_naive_partials(gpu_device):
+    """200 requests x 128 heads: the prefix pass splits its tokens in two (two naive partials per
+    row), and the up-projection takes runs of 3, 3 and 1 blocks of 32 queries through its
+    two-slot ring, the last block with 8 valid rows.  Some requests have no suffix at all (their
+    latent partial is never written and must count as zeros)."""
+    spec = W.small_spec(name="two_naive_partials_h128", dtype="bf16", batch=200, heads=128, q_len=1,
+                        prefix_len=160, suffix_min=0, suffix_max=20, seed=77)
+    wl = W.make_workload(spec)
+    a = wl.as_float64()
+    ref2, ref2_lse = Hh.oracle_absorb_all_heads_parallel(O, a)
+    pairs = [(b, h) for b in (0, 95, 96, 191, 192, 199) for h in (0, 64, 127)]
+    ref, ref_lse = O.mla_decode_definition(**a, pairs=pairs)
+    print("streaming up-projection, two naive partials", flush=True)
+    got, got_lse = Hh.run_library(wl, "mixed", gpu_device)
+    Hh.assert_parity(got, got_lse, ref2, ref2_lse, "bf16", "two_naive/absorb-form")
+    Hh.assert_parity(got, got_lse, ref, ref_lse, "bf16", "two_naive/definition")
 
 
 @pytest.mark.parametrize("mode", MODES)
