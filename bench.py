@@ -258,6 +258,8 @@ def kernel_rooflines(case, stage_ms, C):
                                           "WRITE_SIZE runs of this workload, not this run)"
                                           if roofline["traffic"] is not None else None)
             roofline["algorithmic_bytes"] = w["bytes"]
+            if "bytes_table1" in w:      # the paper's Table 1 accounting of the same pass
+                roofline["algorithmic_bytes_table1"] = w["bytes_table1"]
             roofline["algorithmic_flops"] = w["flops"]
             roofline["kernel_ms"] = stage_ms[dom]
             roofline["mfma_frac"] = w["flops"] / t / MFMA_BF16_PEAK

@@ -113,12 +113,16 @@ int typhoon_mla_expand_pool(const tmla_dims* dims, int32_t num_blocks, int32_t b
 /*
  * Break-even batch size of Section 3.2 ("Fall-back to Absorb" in Section 3.1): TMLA_MODE_AUTO
  * runs mixed when batch >= this value and absorb_only below it.  The paper's closed form,
- * B_theta = (D_qk + D_v) / (q_len (2 D_l + D_r)) * T / M, has the absorb throughput T as a
- * constant; on MI355X a batch near the cross-over is too small to fill the chip, so the effective
- * T depends on the heads per request and on the prefix length.  The library uses a fit to its own
- * measured cross-overs (q_len = 1: 6 at 128 heads / prefix 4096, 28 at 128 / 16384, 7 at
- * 64 / 16384, none -- mixed always wins -- at 16 heads):
- *     B_theta = max(0, 7.3 (H / 128)^1.7 (prefix_len / 4096) - 1.5) / q_len.
+ * B_theta = (D_qk + D_v) / (q_len (2 D_l + D_r)) * T / M, takes the absorb throughput T and the
+ * bandwidth M as constants; on MI355X a batch near the cross-over is too small to fill the chip
+ * in absorb form and short steps are mostly launch latency, so the library interpolates its own
+ * measured cross-overs (q_len = 1) in log2(heads) x log2(prefix_len), clamped at the edges:
+ *     prefix_len   16 heads   32    64   128
+ *        1024        100      45    40     5      (the two modes differ by < 10 % here)
+ *        4096          0       0     0     2      (0: mixed wins at every batch)
+ *       16384          0       0   4.5     8
+ *       65536          0       6    19    22
+ * and divides by q_len.
  * The environment variable TMLA_AUTO_BATCH_THRESHOLD, read once per process, overrides it.
  * Returns -1 on invalid arguments.
  */

@@ -65,12 +65,17 @@ def combine_elements(sh):
 
 # ---- per-kernel algorithmic work (what the method itself must move / compute) ----------------
 def prefix_kernel_work(sh, n_split=1):
-    """Naive shared-prefix pass: expanded K/V once, queries once, partial outputs written."""
+    """Naive shared-prefix pass: expanded K/V once, queries once, partial outputs written.
+
+    The RoPE part of a key is the same for every head; the kernels fetch it from one head's
+    blocks, so per token the pass must move H x (D_n + D_v) + D_r elements, not the
+    H x (D_qk + D_v) of Table 1 (kept as `bytes_table1` for comparison)."""
     rows = sh.B * sh.S_q * sh.H
-    bytes_ = (sh.L_s * sh.H * (D_QK + D_V) * sh.elem_bytes + rows * D_QK * sh.elem_bytes
-              + n_split * rows * (D_V + 1) * 4)
+    other = rows * D_QK * sh.elem_bytes + n_split * rows * (D_V + 1) * 4
+    bytes_ = sh.L_s * (sh.H * (D_N + D_V) + D_R) * sh.elem_bytes + other
+    table1 = sh.L_s * sh.H * (D_QK + D_V) * sh.elem_bytes + other
     flops = 2 * sh.B * sh.S_q * sh.L_s * sh.H * (D_QK + D_V)
-    return dict(bytes=bytes_, flops=flops)
+    return dict(bytes=bytes_, flops=flops, bytes_table1=table1)
 
 
 def suffix_kernel_work(sh, n_partials_rows=0):

@@ -242,17 +242,32 @@ static int check_decode_sizes(const tmla_dims* dims, int mode, int batch, int q_
   return TMLA_OK;
 }
 
-// Section 3.2's break-even batch is B_theta = (D_qk + D_v) / (S_q (2 D_l + D_r)) * T / M.  On this
-// GPU the absorb throughput T over a shared prefix is not a constant near the cross-over: a small
-// batch cannot fill the chip (few requests, each cut into a bounded number of chunks), so the
-// effective T grows with the rows per request (heads) and with the prefix length, while the naive
-// pass streams at M ~ 5.5 TB/s throughout.  Measured cross-overs (bench.py --sweep; batch at which
-// mixed overtakes absorb_only, S_q = 1): 128 heads: 6 at L_s = 4096, 28 at 16384; 64 heads: below 1
-// at 4096, 7 at 16384; 16 heads: mixed wins at every batch.  The fit below reproduces them; in
-// the paper's form it is the closed formula with T_eff = M (2 D_l + D_r) / (D_qk + D_v) * B_theta.
+// Section 3.2's break-even batch is B_theta = (D_qk + D_v) / (S_q (2 D_l + D_r)) * T / M with the
+// absorb throughput T and the memory bandwidth M as constants.  On this GPU neither side is that
+// simple near the cross-over: a small batch cannot fill the chip in absorb form (few requests,
+// each cut into a bounded number of chunks whose partials the combine step then merges), the
+// naive pass streams a prefix of L_s H (D_n + D_v) + L_s D_r elements at ~5.5 TB/s whatever the
+// batch, and below ~50 us a step is mostly launch and fill latencies, where absorb_only has one
+// kernel less.  So the library interpolates its own measured cross-overs (bench.py --sweep,
+// S_q = 1, suffix 512: the batch at which mixed overtakes absorb_only; 0.25 stands for "mixed
+// wins at every batch") in log2(heads) x log2(prefix length), clamped at the table's edges.
 static double fitted_batch_threshold(int heads, int prefix_len) {
-  const double p = 7.3 * std::pow(heads / 128.0, 1.7);
-  return std::max(0.0, p * (prefix_len / 4096.0) - 1.5);
+  static const double cross[4][4] = {
+      //  16     32     64    128 heads
+      {100.0, 45.0, 40.0, 5.0},     // prefix 1024: short steps, the modes differ by < 10 %
+      {0.25, 0.25, 0.5, 2.0},       // prefix 4096
+      {0.25, 0.25, 4.5, 8.0},       // prefix 16384
+      {0.25, 6.0, 19.0, 22.0},      // prefix 65536
+  };
+  const double x = std::min(3.0, std::max(0.0, std::log2(std::max(1, heads) / 16.0)));
+  const double y = std::min(3.0, std::max(0.0, std::log2(std::max(1, prefix_len) / 1024.0) / 2.0));
+  const int x0 = std::min(2, (int)x), y0 = std::min(2, (int)y);
+  const double fx = x - x0, fy = y - y0;
+  auto lg = [&](int r, int c) { return std::log2(cross[r][c]); };
+  const double v = (1 - fy) * ((1 - fx) * lg(y0, x0) + fx * lg(y0, x0 + 1)) +
+                   fy * ((1 - fx) * lg(y0 + 1, x0) + fx * lg(y0 + 1, x0 + 1));
+  const double b = std::exp2(v);
+  return b < 0.75 ? 0.0 : b;
 }
 
 double typhoon_mla_auto_batch_threshold(const tmla_dims* dims, int32_t q_len, int32_t prefix_len) {

@@ -402,7 +402,8 @@ __device__ inline void pl_mfma_o_w(f32x16& d, const bf16x8& a, const bf16x8& b) 
 // set in front of the MFMA, which then fills the wait state the hardware wants between a write
 // of M0 and its use; set next to the transfer it costs an idle issue slot.  Same contract as
 // dma16_scalar_base: wave-uniform base and LDS address, 32-bit per-lane offset.
-template <bool WAIT>
+// STREAM: non-temporal transfer (data nobody else reads).
+template <bool WAIT, bool STREAM>
 __device__ inline void pl_mfma_o_dma(f32x16& d, const bf16x8& a, const bf16x8& b,
                                      uint32_t lane_off, const void* base, uint32_t lds) {
   const uint64_t u = (uint64_t)base;
@@ -410,15 +411,21 @@ __device__ inline void pl_mfma_o_dma(f32x16& d, const bf16x8& a, const bf16x8& b
   const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
   base = (const void*)(((uint64_t)hi << 32) | lo);
   lds = __builtin_amdgcn_readfirstlane(lds);
-  if constexpr (WAIT)
-    asm volatile("s_mov_b32 m0, %5\n\ts_waitcnt lgkmcnt(%6)\n\t"
-                 "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\tglobal_load_lds_dwordx4 %3, %4" TMLA_STREAM_POLICY
-                 : "+a"(d) : "v"(a), "v"(b), "v"(lane_off), "s"(base), "s"(lds), "n"(PL_WAIT)
-                 : "memory");
-  else
-    asm volatile("s_mov_b32 m0, %5\n\t"
-                 "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\tglobal_load_lds_dwordx4 %3, %4" TMLA_STREAM_POLICY
-                 : "+a"(d) : "v"(a), "v"(b), "v"(lane_off), "s"(base), "s"(lds) : "memory");
+#define PL_MFMA_DMA_W(POLICY)                                                                   \
+  asm volatile("s_mov_b32 m0, %5\n\ts_waitcnt lgkmcnt(%6)\n\t"                                  \
+               "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\tglobal_load_lds_dwordx4 %3, %4" POLICY \
+               : "+a"(d) : "v"(a), "v"(b), "v"(lane_off), "s"(base), "s"(lds), "n"(PL_WAIT)      \
+               : "memory")
+#define PL_MFMA_DMA(POLICY)                                                                     \
+  asm volatile("s_mov_b32 m0, %5\n\t"                                                           \
+               "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\tglobal_load_lds_dwordx4 %3, %4" POLICY \
+               : "+a"(d) : "v"(a), "v"(b), "v"(lane_off), "s"(base), "s"(lds) : "memory")
+  if constexpr (WAIT && STREAM) PL_MFMA_DMA_W(TMLA_STREAM_POLICY);
+  else if constexpr (WAIT) PL_MFMA_DMA_W("");
+  else if constexpr (STREAM) PL_MFMA_DMA(TMLA_STREAM_POLICY);
+  else PL_MFMA_DMA("");
+#undef PL_MFMA_DMA_W
+#undef PL_MFMA_DMA
 }
 // enough idle issue slots for the last MFMA (16 passes) to have written its result
 __device__ inline void pl_mfma_drain() {
@@ -462,6 +469,10 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
   // transfers: fragment f of a block is moved by wavefront f % 4 (K: 12 fragments, V: 8)
   const char* kbase = (const char*)(a.pk + ((size_t)h * a.ntb + tb0) * K_BLK_ELEMS);
   const char* vbase = (const char*)(a.pv + ((size_t)h * a.ntb + tb0) * V_BLK_ELEMS);
+  // The RoPE part of a key (fragments 8 .. 11 of a block) is the same for every head: all heads
+  // take it from head 0's blocks, so that it is fetched from HBM once and served from cache to
+  // the other heads (a fifth of the expanded cache's bytes), with the ordinary cache policy.
+  const char* rbase = (const char*)(a.pk + (size_t)tb0 * K_BLK_ELEMS);
   const uint32_t lds_base = lds_addr(smem) + wave * 1024;
   uint32_t lane_off[3];   // fragment w, w + 4, w + 8 of a block
 #pragma unroll
@@ -469,9 +480,14 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
   using GUARD = std::true_type;
   using NOGUARD = std::false_type;
   auto dma_k = [&](int k, int f, auto guard_tag) __attribute__((always_inline)) {
-    if (!decltype(guard_tag)::value || k < nblk)
-      dma16_scalar_base(lane_off[f], kbase + (size_t)k * PL_K_BYTES,
-               lds_base + (k & (PL_NK - 1)) * PL_K_BYTES + f * 4096);
+    if (!decltype(guard_tag)::value || k < nblk) {
+      if (f == 2)
+        dma16_scalar_base<false>(lane_off[f], rbase + (size_t)k * PL_K_BYTES,
+                                 lds_base + (k & (PL_NK - 1)) * PL_K_BYTES + f * 4096);
+      else
+        dma16_scalar_base<true>(lane_off[f], kbase + (size_t)k * PL_K_BYTES,
+                                lds_base + (k & (PL_NK - 1)) * PL_K_BYTES + f * 4096);
+    }
   };
   auto dma_v = [&](int kv, int f, auto guard_tag) __attribute__((always_inline)) {
     if (!decltype(guard_tag)::value || (kv >= 0 && kv < nblk))
@@ -625,12 +641,16 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_pipelined_kernel(PrefixArg
           if constexpr (fused_dma) {
             // transfer d of the group: K fragments w, w + 4, w + 8 of block kg, then V fragments
             // w, w + 4 of block kg - 3
-            if constexpr (d < 3)
-              pl_mfma_o_dma<wait_here>(o[db][nb], fr[cur], p_in[nb][kk], lane_off[d],
-                                       kbase + (size_t)kg * PL_K_BYTES,
-                                       lds_base + (kg & (PL_NK - 1)) * PL_K_BYTES + d * 4096);
+            if constexpr (d < 2)
+              pl_mfma_o_dma<wait_here, true>(o[db][nb], fr[cur], p_in[nb][kk], lane_off[d],
+                                             kbase + (size_t)kg * PL_K_BYTES,
+                                             lds_base + (kg & (PL_NK - 1)) * PL_K_BYTES + d * 4096);
+            else if constexpr (d == 2)
+              pl_mfma_o_dma<wait_here, false>(o[db][nb], fr[cur], p_in[nb][kk], lane_off[d],
+                                              rbase + (size_t)kg * PL_K_BYTES,
+                                              lds_base + (kg & (PL_NK - 1)) * PL_K_BYTES + d * 4096);
             else
-              pl_mfma_o_dma<wait_here>(o[db][nb], fr[cur], p_in[nb][kk], lane_off[d - 3],
+              pl_mfma_o_dma<wait_here, true>(o[db][nb], fr[cur], p_in[nb][kk], lane_off[d - 3],
                                        vbase + (size_t)(kg - 3) * PL_V_BYTES,
                                        lds_base + PL_V_BASE + ((kg - 3) & (PL_NV - 1)) * PL_V_BYTES +
                                            (d - 3) * 4096);
@@ -1005,6 +1025,9 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_token_split_kernel(PrefixA
   const int tb1 = min(PAGED ? (len + TOK_BLK - 1) / TOK_BLK : a.ntb, tb0 + a.blocks_per_split);
   const __bf16* kbase = a.pk + ((size_t)h * a.ntb) * K_BLK_ELEMS + lane * 8;
   const __bf16* vbase = a.pv + ((size_t)h * a.ntb) * V_BLK_ELEMS + lane * 8;
+  // the RoPE part of the keys is the same for every head: taken from head 0's blocks, fetched
+  // from HBM once and served from cache to the other heads
+  const __bf16* rbase = a.pk + lane * 8;
 
   f32x16 o[4][2];
 #pragma unroll
@@ -1027,9 +1050,12 @@ __global__ void __launch_bounds__(256, 1) prefix_attn_token_split_kernel(PrefixA
       ptb = ((size_t)page << a.page_shift) + (tb & ((1 << a.page_shift) - 1));
     }
     const __bf16* ks = kbase + ptb * K_BLK_ELEMS;
+    const __bf16* rs = rbase + ptb * K_BLK_ELEMS;
     const __bf16* vs = vbase + ptb * V_BLK_ELEMS;
 #pragma unroll
-    for (int f = 0; f < 12; f++) dma16_stream(ks + f * 512, dst + f * 1024);
+    for (int f = 0; f < 8; f++) dma16_stream(ks + f * 512, dst + f * 1024);
+#pragma unroll
+    for (int f = 8; f < 12; f++) dma16(rs + f * 512, dst + f * 1024);
 #pragma unroll
     for (int f = 0; f < 8; f++) dma16_stream(vs + f * 512, dst + K_BLK_ELEMS * 2 + f * 1024);
   };

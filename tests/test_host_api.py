@@ -190,19 +190,25 @@ def test_auto_mode_threshold_follows_break_even_formula():
     from paper_2509_21081_amd import cost_model as C
     d128, d64, d16 = _dims(num_heads=128), _dims(num_heads=64), _dims(num_heads=16)
     thr = T.typhoon_mla_auto_batch_threshold
-    # the measured cross-overs the fit was made from (mixed overtakes absorb_only at this batch)
-    assert 5 <= thr(d128, 1, 4096) <= 7
-    assert 24 <= thr(d128, 1, 16384) <= 32
-    assert thr(d64, 1, 4096) <= 1
-    assert 6 <= thr(d64, 1, 16384) <= 9
-    assert thr(d16, 1, 4096) == 0 and thr(d16, 1, 16384) == 0
-    # Section 3.2: the break-even batch falls as 1 / S_q, grows with the prefix and the heads
+    # the measured cross-overs the table holds (mixed overtakes absorb_only at this batch)
+    assert 1 <= thr(d128, 1, 4096) <= 3
+    assert 6 <= thr(d128, 1, 16384) <= 10
+    assert 18 <= thr(d128, 1, 65536) <= 28
+    assert thr(d64, 1, 4096) == 0
+    assert 3 <= thr(d64, 1, 16384) <= 6
+    assert 30 <= thr(d64, 1, 1024) <= 50
+    assert thr(d16, 1, 4096) == 0 and thr(d16, 1, 16384) == 0 and thr(d16, 1, 65536) == 0
+    # clamped outside the table, interpolated geometrically inside
+    assert thr(d128, 1, 100) == thr(d128, 1, 1024) and thr(d128, 1, 1 << 20) == thr(d128, 1, 65536)
+    assert thr(_dims(num_heads=256), 1, 16384) == thr(d128, 1, 16384)
+    assert abs(thr(d128, 1, 8192) - (thr(d128, 1, 4096) * thr(d128, 1, 16384)) ** 0.5) < 1e-9
+    # Section 3.2: the break-even batch falls as 1 / S_q; long prefixes and many heads raise it
     assert abs(thr(d128, 2, 4096) - thr(d128, 1, 4096) / 2) < 1e-9
-    assert thr(d128, 1, 8192) > thr(d128, 1, 4096) > thr(d64, 1, 4096)
+    assert thr(d128, 1, 65536) > thr(d128, 1, 16384) > thr(d128, 1, 4096) > thr(d64, 1, 4096)
     # in the paper's form: the same closed formula with the effective absorb throughput that this
     # threshold implies against the naive pass's 5.5 TB/s -- a small fraction of the bf16 peak
-    t_eff = thr(d128, 1, 4096) * 5.5e12 * (2 * 512 + 64) / (192 + 128)
-    assert abs(C.batch_threshold(t_eff, 5.5e12, 1) - thr(d128, 1, 4096)) < 1e-9
+    t_eff = thr(d128, 1, 16384) * 5.5e12 * (2 * 512 + 64) / (192 + 128)
+    assert abs(C.batch_threshold(t_eff, 5.5e12, 1) - thr(d128, 1, 16384)) < 1e-9
     assert 50e12 < t_eff < 250e12
     assert thr(_dims(kv_lora_rank=256), 1, 4096) == -1
     L = T.lib()
@@ -213,8 +219,8 @@ def test_auto_mode_threshold_follows_break_even_formula():
     assert _decode(L, d, mode=4) == T.TMLA_ERR_INVALID_ARG
     big = T.typhoon_mla_decode_workspace_bytes(d128, T.MODE_AUTO, 64, 1, 4096, 512)
     assert big == T.typhoon_mla_decode_workspace_bytes(d128, T.MODE_MIXED, 64, 1, 4096, 512)
-    small = T.typhoon_mla_decode_workspace_bytes(d128, T.MODE_AUTO, 2, 1, 4096, 512)
-    assert small == T.typhoon_mla_decode_workspace_bytes(d128, T.MODE_ABSORB_ONLY, 2, 1, 4096, 512)
+    small = T.typhoon_mla_decode_workspace_bytes(d128, T.MODE_AUTO, 1, 1, 4096, 512)
+    assert small == T.typhoon_mla_decode_workspace_bytes(d128, T.MODE_ABSORB_ONLY, 1, 1, 4096, 512)
 
 
 def test_tree_decode_validation():

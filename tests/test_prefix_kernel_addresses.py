@@ -52,6 +52,7 @@ def _walk(H, Ls, np_split, p_chunk):
         nfull = nblk - 1 if has_tail else nblk
         kbase = ((H - 1) * ntb + tb0) * KB
         vbase = ((H - 1) * ntb + tb0) * VB
+        rbase = tb0 * KB      # fragments 8 .. 11 (the RoPE part) come from head 0's blocks
         # steady periods: t = 2, 3, ... in pairs while t + 1 + AHEAD < nblk
         steady = set()
         t = 2
@@ -64,7 +65,8 @@ def _walk(H, Ls, np_split, p_chunk):
             if (not guarded) or k < nblk:
                 for f in range(3):
                     for w in range(4):
-                        out.append((when, "K", k, kbase + k * KB + f * 4096 + w * 1024,
+                        out.append((when, "K", k,
+                                    (rbase if f == 2 else kbase) + k * KB + f * 4096 + w * 1024,
                                     (k % NK) * KB + f * 4096 + w * 1024, guarded))
             kv = k - 3
             if (not guarded) or 0 <= kv < nblk:
