@@ -37,6 +37,10 @@
  *     V element (h, t, d), d in [0,128), with u = t%16:
  *        ((((h*NTB + t/32)*2 + (t%32)/16)*4 + d/32)*64 + (d%32) + 32*((u/4)%2))*8 + 4*(u/8) + u%4
  *     i.e. 6144 K elements and 4096 V elements per (head, 32-token block).
+ *     The RoPE part of a key (d in [128,192)) is the same for every head (Algorithm 1: the
+ *     RoPE cache has no head axis); the expansion writes it into every head's blocks, and the
+ *     bf16 decode kernels read it from head 0's blocks for all heads, so that it comes from HBM
+ *     once.  A buffer filled by other means must keep that part identical across heads.
  *   Use typhoon_mla_expanded_k_bytes / _v_bytes for the buffer sizes.
  */
 #ifndef TYPHOON_MLA_H
