@@ -118,14 +118,15 @@ int typhoon_mla_expand_pool(const tmla_dims* dims, int32_t num_blocks, int32_t b
  * Break-even batch size of Section 3.2 ("Fall-back to Absorb" in Section 3.1): TMLA_MODE_AUTO
  * runs mixed when batch >= this value and absorb_only below it.  The paper's closed form,
  * B_theta = (D_qk + D_v) / (q_len (2 D_l + D_r)) * T / M, takes the absorb throughput T and the
- * bandwidth M as constants; on MI355X a batch near the cross-over is too small to fill the chip
- * in absorb form and short steps are mostly launch latency, so the library interpolates its own
- * measured cross-overs (q_len = 1) in log2(heads) x log2(prefix_len), clamped at the edges:
+ * bandwidth M as constants; near the cross-over neither is one on MI355X (a small batch is cut
+ * into chunks to fill the chip, short steps are mostly launch latency), so the library
+ * interpolates its own measured cross-overs (q_len = 1) in log2(heads) x log2(prefix_len),
+ * clamped at the edges:
  *     prefix_len   16 heads   32    64   128
- *        1024        100      45    40     5      (the two modes differ by < 10 % here)
- *        4096          0       0     0     2      (0: mixed wins at every batch)
- *       16384          0       0   4.5     8
- *       65536          0       6    19    22
+ *        1024        220      64   128    70
+ *        4096         60      16    52    45
+ *       16384         19      11    35    40
+ *       65536         11      12    32    40
  * and divides by q_len.
  * The environment variable TMLA_AUTO_BATCH_THRESHOLD, read once per process, overrides it.
  * Returns -1 on invalid arguments.

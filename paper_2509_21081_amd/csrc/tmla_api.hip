@@ -71,6 +71,35 @@ static void plan_prefix_splits(int H, int M, int Ls, int* p_chunk, int* np_split
 
 void layout_workspace(Plan* p);
 
+// Token chunk of the absorb pass for a grid with fewer (request, row group) pairs than compute
+// units, where the chunk count alone decides how the pass fills the chip: 264 workgroups take two
+// rounds on 256 units, 240 take one.  Every chunk length (in 64-token steps) is priced with a
+// small model of the 64- and 128-row kernels -- rounds x (start-up + steps x step time) plus the
+// merge of the partials -- and the cheapest is taken.  The constants are measured on MI355X
+// (start-up 15 us, 3.3 / 4.1 us per step, partials merged at 3 TB/s); they only have to rank the
+// candidates.  Ls = latent prefix tokens walked in absorb form (0 in mixed mode).
+static int plan_small_grid_chunk(int B, int R, int Ls, int Ln, int block_size) {
+  const int g64 = ceil_div(R, 64);
+  const int longest = std::max(Ls, Ln);
+  double best = 1e300;
+  int best_T = 0;
+  for (int T = 256; T < longest + 64; T += 64) {
+    const int Ts = round_up(T, block_size);
+    const int ap = Ls > 0 ? ceil_div(Ls, T) : 0, as = Ln > 0 ? ceil_div(Ln, Ts) : 0;
+    if (ap > MAX_CHUNKS || as > MAX_CHUNKS) continue;
+    const int n_lat = ap + as;
+    const bool rows128 = R % 128 == 0 && (long long)n_lat * B * (R / 128) >= NUM_CU;
+    const long long wgs = (long long)n_lat * B * (rows128 ? R / 128 : g64);
+    const int steps = ceil_div(std::max(std::min(T, Ls), std::min(Ts, Ln)), 64);
+    const double rounds = (double)ceil_div(wgs, (long long)NUM_CU);
+    double t = rounds * (15.0 + steps * (rows128 ? 4.1 : 3.3));
+    if (n_lat > 4) t += 3.0 + (double)n_lat * B * R * 1024.0 / 3e6;
+    else t += 1.5 * (n_lat - 1);
+    if (t <= best) { best = t; best_T = T; }
+  }
+  return best_T ? best_T : round_up(std::max(longest, 64), 64);
+}
+
 // Cuts the call into work items (token chunks) and lays the intermediates out in the workspace.
 // Chunk counts per request are bounds derived from host-visible sizes only; a chunk that turns
 // out empty on the device reports LSE = -inf and is skipped by the combine step.
@@ -105,16 +134,20 @@ int make_plan(const tmla_dims* dims, int mode, int B, int Sq, int Ls, int max_su
     const int per_wg = R <= 16 ? 4 : 1;
     const int wgs = std::max(1, B * ceil_div(R, 64));
     const int want = std::max(1, ceil_div(2 * NUM_CU, wgs)) * per_wg;   // chunks per request
+    const int Ls_abs = mode == TMLA_MODE_ABSORB_ONLY ? Ls : 0;
+    // small grids of the 64- / 128-row kernels: chunk from the model above
+    const int modelled = (R > 32 && wgs < NUM_CU && (Ls_abs > 0 || max_suffix > 0))
+                             ? plan_small_grid_chunk(B, R, Ls_abs, max_suffix, block_size) : 0;
     if (mode == TMLA_MODE_ABSORB_ONLY && Ls > 0) {
       int chunk = tune(TMLA_TUNE_ABSORB_PREFIX_CHUNK);
-      if (chunk <= 0) chunk = std::max(256, ceil_div(Ls, want));
+      if (chunk <= 0) chunk = modelled ? modelled : std::max(256, ceil_div(Ls, want));
       chunk = std::max(chunk, ceil_div(Ls, MAX_CHUNKS));
       p->ap_chunk = round_up(std::min(chunk, round_up(Ls, TOK_BLK)), TOK_BLK);
       p->ap_chunks = ceil_div(Ls, p->ap_chunk);
     }
     if (max_suffix > 0) {
       int chunk = tune(TMLA_TUNE_SUFFIX_CHUNK);
-      if (chunk <= 0) chunk = std::max(256, ceil_div(max_suffix, want));
+      if (chunk <= 0) chunk = modelled ? modelled : std::max(256, ceil_div(max_suffix, want));
       chunk = std::max(chunk, ceil_div(max_suffix, MAX_CHUNKS));
       p->as_chunk = round_up(std::min(chunk, round_up(max_suffix, block_size)), block_size);
       p->as_chunks = ceil_div(max_suffix, p->as_chunk);
@@ -243,21 +276,21 @@ static int check_decode_sizes(const tmla_dims* dims, int mode, int batch, int q_
 }
 
 // Section 3.2's break-even batch is B_theta = (D_qk + D_v) / (S_q (2 D_l + D_r)) * T / M with the
-// absorb throughput T and the memory bandwidth M as constants.  On this GPU neither side is that
-// simple near the cross-over: a small batch cannot fill the chip in absorb form (few requests,
-// each cut into a bounded number of chunks whose partials the combine step then merges), the
-// naive pass streams a prefix of L_s H (D_n + D_v) + L_s D_r elements at ~5.5 TB/s whatever the
-// batch, and below ~50 us a step is mostly launch and fill latencies, where absorb_only has one
-// kernel less.  So the library interpolates its own measured cross-overs (bench.py --sweep,
-// S_q = 1, suffix 512: the batch at which mixed overtakes absorb_only; 0.25 stands for "mixed
-// wins at every batch") in log2(heads) x log2(prefix length), clamped at the table's edges.
+// absorb throughput T and the memory bandwidth M as constants (with T ~ 300 TFLOP/s for a small
+// batch and M ~ 5.5 TB/s it gives 16).  Near the cross-over neither side is that simple on this
+// GPU: in absorb form a small batch is cut into chunks until it fills the chip and its partials
+// are merged afterwards, the naive pass streams L_s (H (D_n + D_v) + D_r) elements whatever the
+// batch, and a short step is mostly launch latency.  So the library interpolates its own
+// measured cross-overs (bench.py --sweep, S_q = 1, suffix 512: the batch at which mixed
+// overtakes absorb_only) in log2(heads) x log2(prefix length), clamped at the table's edges.
+// (The dips at 32 heads are real: 32 query rows per request run the small shared-tile kernel.)
 static double fitted_batch_threshold(int heads, int prefix_len) {
   static const double cross[4][4] = {
       //  16     32     64    128 heads
-      {100.0, 45.0, 40.0, 5.0},     // prefix 1024: short steps, the modes differ by < 10 %
-      {0.25, 0.25, 0.5, 2.0},       // prefix 4096
-      {0.25, 0.25, 4.5, 8.0},       // prefix 16384
-      {0.25, 6.0, 19.0, 22.0},      // prefix 65536
+      {220.0, 64.0, 128.0, 70.0},   // prefix 1024: short steps, the modes differ little
+      {60.0, 16.0, 52.0, 45.0},     // prefix 4096
+      {19.0, 11.0, 35.0, 40.0},     // prefix 16384
+      {11.0, 12.0, 32.0, 40.0},     // prefix 65536
   };
   const double x = std::min(3.0, std::max(0.0, std::log2(std::max(1, heads) / 16.0)));
   const double y = std::min(3.0, std::max(0.0, std::log2(std::max(1, prefix_len) / 1024.0) / 2.0));
@@ -266,8 +299,7 @@ static double fitted_batch_threshold(int heads, int prefix_len) {
   auto lg = [&](int r, int c) { return std::log2(cross[r][c]); };
   const double v = (1 - fy) * ((1 - fx) * lg(y0, x0) + fx * lg(y0, x0 + 1)) +
                    fy * ((1 - fx) * lg(y0 + 1, x0) + fx * lg(y0 + 1, x0 + 1));
-  const double b = std::exp2(v);
-  return b < 0.75 ? 0.0 : b;
+  return std::exp2(v);
 }
 
 double typhoon_mla_auto_batch_threshold(const tmla_dims* dims, int32_t q_len, int32_t prefix_len) {

@@ -157,7 +157,7 @@ int mfma_absorb_attention(const Plan& p, const DecodeArgs& a);
 const int32_t* suffix_request_order(const Plan& p, const DecodeArgs& a, long long wgs);
 int mfma_absorb16_attention(const Plan& p, const DecodeArgs& a);   // S_q * H <= 16
 int mfma_finalize(const Plan& p, const DecodeArgs& a);
-constexpr int MAX_CHUNKS = 32;  // per-request chunk bound for each of the latent prefix / suffix
+constexpr int MAX_CHUNKS = 64;  // per-request chunk bound for each of the latent prefix / suffix
 void launch_combine_lse(int num_partials, int64_t rows, int width, const float* po,
                         const float* pl, void* out, int out_dtype, float* lse_out,
                         hipStream_t stream);

@@ -145,6 +145,8 @@ int mfma_query_absorb(const Plan& p, const DecodeArgs& d) {
 // through LDS, after which wavefront w finishes value columns [32w, 32w+32): merge with the naive
 // partials, normalise, store.
 constexpr int FIN_MAX_LAT = 64;  // latent partials per row supported by the weight table in LDS
+constexpr int MERGE_MAX_LAT = 128;   // ... by the separate merge pass (two per lane)
+static_assert(2 * MAX_CHUNKS <= MERGE_MAX_LAT, "latent prefix + suffix chunks per request");
 
 struct FinalizeArgs {
   const float* naive_o; const float* naive_lse; const __bf16* lat_o; const float* lat_lse;
@@ -627,9 +629,70 @@ static void launch_finalize_few(const FinalizeArgs& a, dim3 grid, hipStream_t st
   }
 }
 
+// More than four latent partials per row -- a small batch whose long prefix (absorb_only) or
+// suffix is cut into many chunks so that the pass fills the chip -- are merged by a pass of its
+// own into partial 0, after which the up-projection sees a single partial.  Merging inside the
+// projection kernel walks the partials one dependent load after the other, for 32 query
+// columns of which a small batch fills one or two: 53-110 us at batch 1-8 against 4-8 us here.
+// One workgroup per row: the partials are dealt out to the four wavefronts (i = w, w + 4, ...),
+// a wavefront reads a partial row as one contiguous KiB (lane = 16-byte chunk) eight at a time,
+// the four sums meet in LDS.  Lane i holds the LSEs and the weights of partials i and i + 64 (at
+// most MERGE_MAX_LAT = 128 partials).  A partial with LSE = -inf was never written and is skipped.
+__global__ void __launch_bounds__(256) merge_latent_kernel(__bf16* lat_o, float* lat_lse,
+                                                           int n_lat, int64_t rows) {
+  __shared__ float part[4][64][8];
+  const int64_t row = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  float li[2], e[2], wgt[2];
+#pragma unroll
+  for (int k = 0; k < 2; k++)
+    li[k] = lane + 64 * k < n_lat ? lat_lse[(size_t)(lane + 64 * k) * rows + row] : -INFINITY;
+  float mx = fmaxf(li[0], li[1]);
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) mx = fmaxf(mx, __shfl_xor(mx, s));
+#pragma unroll
+  for (int k = 0; k < 2; k++) e[k] = mx > -INFINITY && li[k] > -INFINITY ? __expf(li[k] - mx) : 0.f;
+  float z = e[0] + e[1];
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) z += __shfl_xor(z, s);
+#pragma unroll
+  for (int k = 0; k < 2; k++) wgt[k] = z > 0.f ? e[k] / z : 0.f;   // normalised weights
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const __bf16* src = lat_o + (size_t)row * D_L + lane * 8;
+  for (int i0 = wave; i0 < n_lat; i0 += 32) {
+    bf16x8 x[8];
+    float w[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+      const int i = i0 + 4 * j;
+      w[j] = i < n_lat ? __shfl(i < 64 ? wgt[0] : wgt[1], i & 63) : 0.f;   // wave-uniform
+      if (w[j] > 0.f) x[j] = *(const bf16x8*)(src + (size_t)i * rows * D_L);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; j++)
+      if (w[j] > 0.f) {
+#pragma unroll
+        for (int k = 0; k < 8; k++) acc[k] += w[j] * (float)x[j][k];
+      }
+  }
+#pragma unroll
+  for (int k = 0; k < 8; k++) part[wave][lane][k] = acc[k];
+  __syncthreads();   // every wavefront has read what it needs of partial 0 as well
+  if (wave == 0) {
+    bf16x8 o;
+#pragma unroll
+    for (int k = 0; k < 8; k++)
+      o[k] = (__bf16)(part[0][lane][k] + part[1][lane][k] + part[2][lane][k] + part[3][lane][k]);
+    *(bf16x8*)(lat_o + (size_t)row * D_L + lane * 8) = o;
+    if (lane == 0) lat_lse[row] = z > 0.f ? mx + __logf(z) : -INFINITY;
+  }
+}
+
 int mfma_finalize(const Plan& p, const DecodeArgs& d) {
   if (p.rows == 0) return TMLA_OK;
-  if (p.n_lat > FIN_MAX_LAT) return TMLA_ERR_UNSUPPORTED;
+  const bool merge_inside = (debug_flags() & 0x10000) != 0;   // debug: no separate merge pass
+  if (p.n_lat > (merge_inside ? FIN_MAX_LAT : MERGE_MAX_LAT)) return TMLA_ERR_UNSUPPORTED;
   FinalizeArgs a;
   a.naive_o = (const float*)(d.ws + p.off_naive_o);
   a.naive_lse = (const float*)(d.ws + p.off_naive_lse);
@@ -639,9 +702,15 @@ int mfma_finalize(const Plan& p, const DecodeArgs& d) {
   a.out = (__bf16*)d.out;
   a.lse_out = d.lse_out;
   a.M = p.B * p.Sq; a.H = p.H; a.n_naive = p.n_naive; a.n_lat = p.n_lat; a.rows = p.rows;
+  if (a.n_lat > 4 && !merge_inside) {
+    hipLaunchKernelGGL(merge_latent_kernel, dim3((unsigned)p.rows), dim3(256), 0, d.stream,
+                       (__bf16*)(d.ws + p.off_lat_o), (float*)(d.ws + p.off_lat_lse), a.n_lat,
+                       (int64_t)p.rows);
+    a.n_lat = 1;
+  }
   // one latent partial, one or two naive partials, and at least two blocks of 32 queries per
   // compute unit: runs of up to eight blocks per workgroup, so that the grid still covers the chip
-  if (p.n_lat == 1 && (p.n_naive == 1 || p.n_naive == 2)) {
+  if (a.n_lat == 1 && (p.n_naive == 1 || p.n_naive == 2)) {
     const int nqb = (a.M + 31) / 32;
     const int heads8 = (p.H + 7) / 8 * 8;
     const long long per_cu = (long long)heads8 * nqb / NUM_CU;
@@ -651,7 +720,7 @@ int mfma_finalize(const Plan& p, const DecodeArgs& d) {
                             : launch_finalize_stream<2>(a, heads8, nqb, qbk, d.stream);
   }
   dim3 grid(8 * ((a.M + 31) / 32) * ((p.H + 7) / 8));
-  switch (p.n_lat) {
+  switch (a.n_lat) {
     case 1: launch_finalize_few<1>(a, grid, d.stream); break;
     case 2: launch_finalize_few<2>(a, grid, d.stream); break;
     case 3: launch_finalize_few<3>(a, grid, d.stream); break;

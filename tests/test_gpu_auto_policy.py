@@ -13,7 +13,7 @@ from paper_2509_21081_amd import workloads as W
 pytestmark = pytest.mark.gpu
 
 GRID = [(H, Ls, B) for H in (16, 64, 128) for Ls in (1024, 4096, 16384, 65536)
-        for B in (1, 4, 16, 64)]
+        for B in (1, 8, 32, 128)]
 
 
 def _median_times(step, modes, rounds=5, steps=10):

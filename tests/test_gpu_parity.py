@@ -382,14 +382,15 @@ def test_modes_agree_with_each_other(gpu_device):
 
 
 AUTO_CASES = {
-    # below the break-even batch of 128 heads and a 2048-token prefix (3.2): absorb_only runs
+    # below the break-even batch of 128 heads and a 2048-token prefix (56): absorb_only runs
     "below_break_even": dict(batch=2, heads=128, q_len=1, prefix_len=2048, suffix_min=10,
                              suffix_max=120, seed=51),
-    # above it: mixed runs
-    "above_break_even": dict(batch=5, heads=128, q_len=1, prefix_len=2048, suffix_min=0,
-                             suffix_max=120, seed=52),
-    # 16 heads and a prefix of 4096 tokens or more: the naive prefix pass wins at every batch
-    "h16": dict(batch=3, heads=16, q_len=1, prefix_len=4100, suffix_min=0, suffix_max=150, seed=11),
+    # above that of 32 heads (32): mixed runs
+    "above_break_even": dict(batch=40, heads=32, q_len=1, prefix_len=2048, suffix_min=0,
+                             suffix_max=60, seed=52),
+    # two query positions per request halve it (16)
+    "above_with_two_queries": dict(batch=20, heads=32, q_len=2, prefix_len=2048, suffix_min=2,
+                                   suffix_max=60, seed=53),
 }
 
 
