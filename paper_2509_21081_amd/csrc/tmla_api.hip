@@ -61,7 +61,7 @@ static inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p % 
 
 // Token splits of a naive pass over Ls shared tokens for M queries per head.
 static void plan_prefix_splits(int H, int M, int Ls, int* p_chunk, int* np_split) {
-  const int wgs = std::max(1, H * (M > 128 ? ceil_div(M, 256) : ceil_div(M, 64)));
+  const int wgs = std::max(1, H * (M > PIPELINED_MIN_M ? ceil_div(M, 256) : ceil_div(M, 64)));
   int splits = tune(TMLA_TUNE_PREFIX_SPLITS);
   if (splits <= 0) splits = std::max(1, NUM_CU / wgs);
   splits = std::max(1, std::min(splits, ceil_div(Ls, 128)));

@@ -157,6 +157,11 @@ int mfma_absorb_attention(const Plan& p, const DecodeArgs& a);
 const int32_t* suffix_request_order(const Plan& p, const DecodeArgs& a, long long wgs);
 int mfma_absorb16_attention(const Plan& p, const DecodeArgs& a);   // S_q * H <= 16
 int mfma_finalize(const Plan& p, const DecodeArgs& a);
+// more queries per head than this: the software-pipelined prefix kernel (256 queries per
+// workgroup); up to this many: the token-split kernel (64 queries per workgroup, the query groups
+// of a head sharing its cache through L2).  Measured with the bound at 64: equal at 4096-token
+// prefixes, 7 % less kernel time at 32768 tokens but a longer step (more partials to combine).
+constexpr int PIPELINED_MIN_M = 128;
 constexpr int MAX_CHUNKS = 64;  // per-request chunk bound for each of the latent prefix / suffix
 void launch_combine_lse(int num_partials, int64_t rows, int width, const float* po,
                         const float* pl, void* out, int out_dtype, float* lse_out,

@@ -1172,12 +1172,12 @@ int mfma_prefix_attention(const Plan& p, const DecodeArgs& d) {
   a.rows = p.rows;
   a.c = d.sm_scale * LOG2E;
   static LdsOptIn lds_pl, lds_qs, lds_ts;
-  if (a.M > 128 && !(debug_flags() & 0x400)) {
+  if (a.M > PIPELINED_MIN_M && !(debug_flags() & 0x400)) {
     if (lds_pl.ensure((const void*)prefix_attn_pipelined_kernel, PL_LDS_BYTES) != hipSuccess)
       return TMLA_ERR_HIP;
     dim3 grid(p.H, (a.M + PL_QUERIES - 1) / PL_QUERIES, p.np_split);
     hipLaunchKernelGGL(prefix_attn_pipelined_kernel, grid, dim3(256), PL_LDS_BYTES, d.stream, a);
-  } else if (a.M > 128) {
+  } else if (a.M > PIPELINED_MIN_M) {
     if (lds_qs.ensure((const void*)prefix_attn_query_split_kernel<1>, QS_LDS_BYTES) != hipSuccess)
       return TMLA_ERR_HIP;
     dim3 grid(p.H, (a.M + QS_QUERIES - 1) / QS_QUERIES, p.np_split);
