@@ -103,6 +103,27 @@ def test_forced_small_chunks(case, mode, gpu_device, tune):
                      logit_gain=wl.spec.q_gain)
 
 
+@pytest.mark.parametrize("flags", [0, 0x10000], ids=["merge_pass", "merge_inside"])
+@pytest.mark.parametrize("mode", ["mixed", "absorb_only"])
+def test_many_latent_partials_small_batch(mode, flags, gpu_device):
+    """One and three requests of 128 heads over a 5000-token prefix and suffixes of up to 3000
+    tokens: the plan cuts the tokens into many chunks to fill the chip (tens of latent partials per
+    row, some empty for the shorter suffix), which the separate merge pass folds into one before
+    the up-projection -- or, with debug flag bit 16, the projection kernel merges itself."""
+    for batch, seed in ((1, 61), (3, 62)):
+        spec = W.small_spec(name=f"many_partials_b{batch}", dtype="bf16", batch=batch, heads=128,
+                            q_len=1, prefix_len=5000, suffix_min=700, suffix_max=3000, seed=seed)
+        wl = W.make_workload(spec)
+        a = wl.as_float64()
+        ref2, ref2_lse = Hh.oracle_absorb_all_heads_parallel(O, a)
+        pairs = [(b, h) for b in range(batch) for h in (0, 77, 127)]
+        ref, ref_lse = O.mla_decode_definition(**a, pairs=pairs)
+        print(f"many partials batch={batch} mode={mode} flags={flags:#x}", flush=True)
+        got, got_lse = Hh.run_library(wl, mode, gpu_device, flags=flags)
+        Hh.assert_parity(got, got_lse, ref2, ref2_lse, "bf16", f"many_partials/{mode}/absorb-form")
+        Hh.assert_parity(got, got_lse, ref, ref_lse, "bf16", f"many_partials/{mode}/definition")
+
+
 @pytest.mark.parametrize("flags", [0, 0x400], ids=["pipelined", "8-wave"])
 @pytest.mark.parametrize("prefix_len", [31, 32, 40, 288, 1024, 1100])
 def test_pipelined_prefix_kernel_long_runs(prefix_len, flags, gpu_device, tune):
