@@ -157,6 +157,8 @@ size_t typhoon_mla_decode_workspace_bytes(const tmla_dims* dims, int32_t mode, i
  * Visibility: every query sees the whole prefix; query position s of request b sees suffix
  * tokens j <= suffix_lens[b] - q_len + s (the suffix already holds the q_len new tokens).
  * A query that sees no token yields zeros and LSE = -inf.
+ * Limits (TMLA_ERR_UNSUPPORTED beyond them): q_len <= 8, batch * q_len * H <= 2^30,
+ * prefix_len and max_suffix_len <= 2^30.
  */
 int typhoon_mla_decode(const tmla_dims* dims, int32_t mode, int32_t batch, int32_t q_len,
                        const void* q, int32_t prefix_len,

@@ -83,7 +83,11 @@ static int plan_small_grid_chunk(int B, int R, int Ls, int Ln, int block_size) {
   const int longest = std::max(Ls, Ln);
   double best = 1e300;
   int best_T = 0;
-  for (int T = 256; T < longest + 64; T += 64) {
+  // candidates: the longer part cut into n = 1 ... MAX_CHUNKS equal chunks of whole 64-token steps
+  // (chunks under 256 tokens are not worth a partial)
+  for (int n = 1; n <= MAX_CHUNKS; n++) {
+    const int T = (int)((((int64_t)longest + n - 1) / n + 63) / 64 * 64);
+    if (n > 1 && T < 256) break;
     const int Ts = round_up(T, block_size);
     const int ap = Ls > 0 ? ceil_div(Ls, T) : 0, as = Ln > 0 ? ceil_div(Ln, Ts) : 0;
     if (ap > MAX_CHUNKS || as > MAX_CHUNKS) continue;
@@ -91,11 +95,11 @@ static int plan_small_grid_chunk(int B, int R, int Ls, int Ln, int block_size) {
     const bool rows128 = R % 128 == 0 && (long long)n_lat * B * (R / 128) >= NUM_CU;
     const long long wgs = (long long)n_lat * B * (rows128 ? R / 128 : g64);
     const int steps = ceil_div(std::max(std::min(T, Ls), std::min(Ts, Ln)), 64);
-    const double rounds = (double)ceil_div(wgs, (long long)NUM_CU);
+    const double rounds = (double)((wgs + NUM_CU - 1) / NUM_CU);
     double t = rounds * (15.0 + steps * (rows128 ? 4.1 : 3.3));
     if (n_lat > 4) t += 3.0 + (double)n_lat * B * R * 1024.0 / 3e6;
     else t += 1.5 * (n_lat - 1);
-    if (t <= best) { best = t; best_T = T; }
+    if (t < best) { best = t; best_T = T; }   // ties: the longer chunk
   }
   return best_T ? best_T : round_up(std::max(longest, 64), 64);
 }
@@ -272,6 +276,8 @@ static int check_decode_sizes(const tmla_dims* dims, int mode, int batch, int q_
   if (batch < 0 || q_len <= 0 || prefix_len < 0 || max_suffix_len < 0) return TMLA_ERR_INVALID_ARG;
   if (q_len > 8) return TMLA_ERR_UNSUPPORTED;
   if ((int64_t)batch * q_len * dims->num_heads > (int64_t)1 << 30) return TMLA_ERR_UNSUPPORTED;
+  // (token counts are rounded up to blocks and chunks in 32-bit arithmetic)
+  if (prefix_len > 1 << 30 || max_suffix_len > 1 << 30) return TMLA_ERR_UNSUPPORTED;
   return TMLA_OK;
 }
 

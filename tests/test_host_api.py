@@ -95,6 +95,7 @@ def test_decode_validation_without_gpu():
     assert _decode(L, d, mode=5) == T.TMLA_ERR_INVALID_ARG
     assert _decode(L, d, q_len=0) == T.TMLA_ERR_INVALID_ARG
     assert _decode(L, d, q_len=9) == T.TMLA_ERR_UNSUPPORTED
+    assert _decode(L, d, prefix_len=(1 << 30) + 1, ws_bytes=1 << 20) == T.TMLA_ERR_UNSUPPORTED
     assert _decode(L, d, batch=-1) == T.TMLA_ERR_INVALID_ARG
     assert _decode(L, d, prefix_len=-3) == T.TMLA_ERR_INVALID_ARG
     assert _decode(L, d, block_size=32) == T.TMLA_ERR_UNSUPPORTED
@@ -117,6 +118,8 @@ def test_decode_validation_without_gpu():
 def test_workspace_bytes_monotone_and_zero_on_error():
     d = _dims(num_heads=128)
     assert T.typhoon_mla_decode_workspace_bytes(d, 7, 4, 1, 10, 10) == 0
+    assert T.typhoon_mla_decode_workspace_bytes(d, T.MODE_MIXED, 1, 1, 2_000_000_000, 10) == 0
+    assert T.typhoon_mla_decode_workspace_bytes(d, T.MODE_ABSORB_ONLY, 1, 1, 1 << 30, 1 << 30) > 0
     small = T.typhoon_mla_decode_workspace_bytes(d, T.MODE_MIXED, 4, 1, 256, 64)
     big = T.typhoon_mla_decode_workspace_bytes(d, T.MODE_MIXED, 64, 1, 4096, 512)
     assert 0 < small < big
