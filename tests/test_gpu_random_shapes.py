@@ -32,7 +32,25 @@ def _specs(count=48, seed=2024):
     return out
 
 
-SPECS = _specs()
+def _wide_specs(count=10, seed=77):
+    """Many requests, few tokens: the large-grid kernels (pipelined prefix pass, streaming
+    up-projection, multi-block query absorption) with ragged query counts."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(count):
+        heads = int(rng.choice([16, 32, 64, 128]))
+        q_len = int(rng.choice([1, 1, 2]))
+        batch = int(rng.integers(130, 40000 // (heads * q_len) + 131))
+        prefix_len = int(rng.integers(129, 420))
+        suffix_max = int(rng.integers(q_len, 48))
+        out.append(dict(name=f"wide_{i}", dtype="bf16", batch=batch, heads=heads, q_len=q_len,
+                        prefix_len=prefix_len, suffix_min=int(rng.integers(0, suffix_max + 1)),
+                        suffix_max=suffix_max, block_size=int(rng.choice([64, 128])),
+                        seed=2000 + i))
+    return out
+
+
+SPECS = _specs() + _wide_specs()
 
 
 @pytest.mark.parametrize("idx", range(len(SPECS)))
